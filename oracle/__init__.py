@@ -1,0 +1,168 @@
+"""CPU oracle for the TP=k -> TP=k' reshard (TEST INFRASTRUCTURE ONLY).
+
+Thin ctypes driver around ``amoeba_oracle.cpp`` operating on numpy arrays in
+host memory.  Only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import this package; the product
+package never does.  The arithmetic lives in the C++ file, which cites the
+paper passages it follows (Sec. 2.2, Sec. 3.1 head-range rule and layouts,
+Sec. 3.2 Eq. (1)).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "amoeba_oracle.cpp")
+_LIB = os.path.join(_HERE, "libamoeba_oracle.so")
+
+HEAD_MAJOR = 0
+TOKEN_MAJOR = 1
+
+OK, ERR_ARG, ERR_OVERFLOW, ERR_BLOCK_ID = 0, 1, 2, 3
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ -O2 (no threads, no intrinsics)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(
+        os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_HERE, "amoeba_oracle.h")))
+    if force or stale:
+        subprocess.check_call(
+            ["g++", "-std=c++17", "-O2", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", _LIB, _SRC])
+    return _LIB
+
+
+class _Model(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn_dim",
+                 "elem_bytes")]
+
+
+class _KV(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("kv_layers", "n_kv_heads", "head_dim", "elem_bytes", "block_tokens",
+                 "layout_src", "layout_dst", "num_seqs", "max_blocks_per_seq")] + \
+               [("src_pool_blocks", ctypes.c_int64), ("dst_pool_blocks", ctypes.c_int64)]
+
+
+@dataclass(frozen=True)
+class Model:
+    n_layers: int
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ffn_dim: int
+    elem_bytes: int = 2
+
+    def _c(self):
+        return _Model(self.n_layers, self.hidden, self.n_q_heads, self.n_kv_heads, self.head_dim,
+                      self.ffn_dim, self.elem_bytes)
+
+
+@dataclass(frozen=True)
+class KV:
+    kv_layers: int
+    n_kv_heads: int
+    head_dim: int
+    block_tokens: int
+    num_seqs: int
+    max_blocks_per_seq: int
+    src_pool_blocks: int
+    dst_pool_blocks: int
+    layout_src: int = HEAD_MAJOR
+    layout_dst: int = HEAD_MAJOR
+    elem_bytes: int = 2
+
+    def _c(self):
+        return _KV(self.kv_layers, self.n_kv_heads, self.head_dim, self.elem_bytes,
+                   self.block_tokens, self.layout_src, self.layout_dst, self.num_seqs,
+                   self.max_blocks_per_seq, self.src_pool_blocks, self.dst_pool_blocks)
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        L.ao_shard_elems.restype = ctypes.c_int64
+        L.ao_shard_elems.argtypes = [ctypes.POINTER(_Model), ctypes.c_int]
+        L.ao_kv_block_elems.restype = ctypes.c_int64
+        L.ao_kv_block_elems.argtypes = [ctypes.POINTER(_KV), ctypes.c_int]
+        L.ao_reshard_weights.restype = ctypes.c_int
+        L.ao_reshard_weights.argtypes = [ctypes.POINTER(_Model), ctypes.c_int, ctypes.c_int,
+                                         ctypes.c_int, ctypes.POINTER(ctypes.c_void_p),
+                                         ctypes.c_void_p]
+        L.ao_reshard_kv.restype = ctypes.c_int
+        L.ao_reshard_kv.argtypes = [ctypes.POINTER(_KV), ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                    ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p,
+                                    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                    ctypes.POINTER(ctypes.c_int64)]
+        _lib = L
+    return _lib
+
+
+_DT = {1: np.uint8, 2: np.uint16, 4: np.uint32}
+
+
+def elem_dtype(elem_bytes: int):
+    return _DT[elem_bytes]
+
+
+def shard_elems(m: Model, tp: int) -> int:
+    return int(lib().ao_shard_elems(ctypes.byref(m._c()), tp))
+
+
+def kv_block_elems(c: KV, tp: int) -> int:
+    return int(lib().ao_kv_block_elems(ctypes.byref(c._c()), tp))
+
+
+def _ptr_array(arrs, n, dtype):
+    out = (ctypes.c_void_p * n)()
+    keep = []
+    for i in range(n):
+        a = arrs[i] if i < len(arrs) else None
+        if a is None:
+            out[i] = None
+        else:
+            assert a.dtype == dtype and a.flags["C_CONTIGUOUS"], "oracle wants contiguous arrays"
+            keep.append(a)
+            out[i] = a.ctypes.data
+    return out, keep
+
+
+def reshard_weights(m: Model, src_tp: int, dst_tp: int, dst_rank: int, src_shards, dst=None):
+    """src_shards: list of src_tp 1-D arrays (opaque elements) or None.  Returns (status, dst)."""
+    dt = elem_dtype(m.elem_bytes)
+    n = shard_elems(m, dst_tp)
+    if dst is None:
+        dst = np.zeros(max(n, 0), dtype=dt)
+    ptrs, _keep = _ptr_array(src_shards, max(src_tp, 1), dt)
+    st = lib().ao_reshard_weights(ctypes.byref(m._c()), src_tp, dst_tp, dst_rank, ptrs,
+                                  dst.ctypes.data)
+    return int(st), dst
+
+
+def reshard_kv(c: KV, src_tp: int, dst_tp: int, dst_rank: int, src_pools, src_table, seq_lens,
+               dst_pool, dst_table=None):
+    """src_pools: list of src_tp arrays [kv_layers, src_pool_blocks, block_elems] or None.
+    dst_pool is written in place.  Returns (status, dst_table, total_blocks)."""
+    dt = elem_dtype(c.elem_bytes)
+    src_table = np.ascontiguousarray(src_table, dtype=np.int32)
+    seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    if dst_table is None:
+        dst_table = np.full((c.num_seqs, c.max_blocks_per_seq), -7, dtype=np.int32)
+    assert dst_table.dtype == np.int32 and dst_table.flags["C_CONTIGUOUS"]
+    assert dst_pool.dtype == dt and dst_pool.flags["C_CONTIGUOUS"]
+    ptrs, _keep = _ptr_array(src_pools, max(src_tp, 1), dt)
+    total = ctypes.c_int64(-1)
+    st = lib().ao_reshard_kv(ctypes.byref(c._c()), src_tp, dst_tp, dst_rank, ptrs,
+                             src_table.ctypes.data, seq_lens.ctypes.data, dst_pool.ctypes.data,
+                             dst_table.ctypes.data, ctypes.byref(total))
+    return int(st), dst_table, int(total.value)

@@ -1,0 +1,258 @@
+// CPU oracle (TEST INFRASTRUCTURE ONLY): per-element definition of the TP=k ->
+// TP=k' reshard of decoder weights and of the paged KV cache.  Single thread,
+// no blocking, no shared code with the HIP library.  See amoeba_oracle.h for
+// the paper passages each part follows.
+#include "amoeba_oracle.h"
+
+#include <cstddef>
+#include <cstdint>
+#include <cstring>
+
+namespace {
+
+bool divides(int tp, int64_t n) { return tp > 0 && n % tp == 0; }
+
+bool model_ok(const ao_model* m) {
+  return m && m->n_layers > 0 && m->hidden > 0 && m->n_q_heads > 0 && m->n_kv_heads > 0 &&
+         m->head_dim > 0 && m->ffn_dim > 0 &&
+         (m->elem_bytes == 1 || m->elem_bytes == 2 || m->elem_bytes == 4) &&
+         m->n_q_heads % m->n_kv_heads == 0;
+}
+
+bool tp_ok(const ao_model* m, int tp) {
+  return divides(tp, m->n_q_heads) && divides(tp, m->n_kv_heads) && divides(tp, m->ffn_dim);
+}
+
+// Geometry of one rank's per-layer shard at TP=t (element offsets inside a layer).
+struct ShardGeom {
+  int64_t q_rows, kv_rows, ffn_rows;  // rows of Wq / Wk,Wv / Wg,Wu held by one rank
+  int64_t o_cols, down_cols;          // columns of Wo / Wd held by one rank
+  int64_t off_qkv, off_o, off_gate_up, off_down, layer_elems;
+};
+
+ShardGeom geom(const ao_model* m, int t) {
+  ShardGeom g;
+  const int64_t H = m->hidden, d = m->head_dim;
+  g.q_rows = (int64_t)m->n_q_heads * d / t;
+  g.kv_rows = (int64_t)m->n_kv_heads * d / t;
+  g.ffn_rows = (int64_t)m->ffn_dim / t;
+  g.o_cols = g.q_rows;
+  g.down_cols = g.ffn_rows;
+  g.off_qkv = 0;
+  g.off_o = g.off_qkv + (g.q_rows + 2 * g.kv_rows) * H;
+  g.off_gate_up = g.off_o + H * g.o_cols;
+  g.off_down = g.off_gate_up + 2 * g.ffn_rows * H;
+  g.layer_elems = g.off_down + H * g.down_cols;
+  return g;
+}
+
+// Sec. 3.2: a tensor cut along stored rows (q, k, v, gate, up).  `rows_total`
+// is the unsharded row count; the sub-block starts `sub_src` / `sub_dst`
+// elements into the fused per-rank tensor on either side.
+template <typename E>
+void gather_row_cut(const E* const* src, E* dst, int64_t src_layer_base, int64_t dst_layer_base,
+                    int64_t sub_src, int64_t sub_dst, int64_t rows_total, int64_t cols, int k,
+                    int kp, int rp) {
+  const int64_t rows_src = rows_total / k, rows_dst = rows_total / kp;
+  for (int64_t rho = 0; rho < rows_dst; ++rho) {
+    const int64_t g = (int64_t)rp * rows_dst + rho;  // row in the unsharded tensor
+    const int64_t s = g / rows_src;                  // owning source rank
+    const int64_t lr = g % rows_src;                 // row inside that rank's sub-block
+    const E* from = src[s] + src_layer_base + sub_src + lr * cols;
+    E* to = dst + dst_layer_base + sub_dst + rho * cols;
+    for (int64_t j = 0; j < cols; ++j) to[j] = from[j];
+  }
+}
+
+// Sec. 3.2: a tensor cut along stored columns (o_proj, down_proj).
+template <typename E>
+void gather_col_cut(const E* const* src, E* dst, int64_t src_layer_base, int64_t dst_layer_base,
+                    int64_t t_src, int64_t t_dst, int64_t rows, int64_t cols_total, int k, int kp,
+                    int rp) {
+  const int64_t cols_src = cols_total / k, cols_dst = cols_total / kp;
+  for (int64_t i = 0; i < rows; ++i) {
+    for (int64_t c = 0; c < cols_dst; ++c) {
+      const int64_t g = (int64_t)rp * cols_dst + c;  // column in the unsharded tensor
+      const int64_t s = g / cols_src;
+      const int64_t lc = g % cols_src;
+      dst[dst_layer_base + t_dst + i * cols_dst + c] =
+          src[s][src_layer_base + t_src + i * cols_src + lc];
+    }
+  }
+}
+
+template <typename E>
+int reshard_weights_t(const ao_model* m, int k, int kp, int rp, const void* const* src_v,
+                      void* dst_v) {
+  const ShardGeom gs = geom(m, k), gd = geom(m, kp);
+  const int64_t H = m->hidden, d = m->head_dim;
+  const int64_t Nq = (int64_t)m->n_q_heads * d, Nkv = (int64_t)m->n_kv_heads * d, I = m->ffn_dim;
+
+  // Which source ranks hold something of the target?  (Needed ones must be non-NULL.)
+  const E* src[64];
+  for (int s = 0; s < k; ++s) src[s] = static_cast<const E*>(src_v[s]);
+  for (int s = 0; s < k; ++s) {
+    bool needed = false;
+    const int64_t tot[3] = {Nq, Nkv, I};
+    for (int a = 0; a < 3; ++a) {
+      const int64_t lo = rp * (tot[a] / kp), hi = lo + tot[a] / kp;
+      const int64_t slo = s * (tot[a] / k), shi = slo + tot[a] / k;
+      if (lo < shi && slo < hi) needed = true;
+    }
+    if (needed && !src[s]) return AO_ERR_ARG;
+  }
+  E* dst = static_cast<E*>(dst_v);
+
+  for (int64_t l = 0; l < m->n_layers; ++l) {
+    const int64_t sb = l * gs.layer_elems, db = l * gd.layer_elems;
+    // fused qkv: [q_r ; k_r ; v_r], each cut along rows by head ranges
+    gather_row_cut(src, dst, sb, db, gs.off_qkv, gd.off_qkv, Nq, H, k, kp, rp);
+    gather_row_cut(src, dst, sb, db, gs.off_qkv + gs.q_rows * H, gd.off_qkv + gd.q_rows * H, Nkv,
+                   H, k, kp, rp);
+    gather_row_cut(src, dst, sb, db, gs.off_qkv + (gs.q_rows + gs.kv_rows) * H,
+                   gd.off_qkv + (gd.q_rows + gd.kv_rows) * H, Nkv, H, k, kp, rp);
+    // o_proj: cut along columns (input features = q heads)
+    gather_col_cut(src, dst, sb, db, gs.off_o, gd.off_o, H, Nq, k, kp, rp);
+    // fused gate_up: [g_r ; u_r], each cut along rows
+    gather_row_cut(src, dst, sb, db, gs.off_gate_up, gd.off_gate_up, I, H, k, kp, rp);
+    gather_row_cut(src, dst, sb, db, gs.off_gate_up + gs.ffn_rows * H,
+                   gd.off_gate_up + gd.ffn_rows * H, I, H, k, kp, rp);
+    // down_proj: cut along columns
+    gather_col_cut(src, dst, sb, db, gs.off_down, gd.off_down, H, I, k, kp, rp);
+  }
+  return AO_OK;
+}
+
+bool kv_ok(const ao_kv* c) {
+  return c && c->kv_layers > 0 && c->n_kv_heads > 0 && c->head_dim > 0 && c->block_tokens > 0 &&
+         (c->elem_bytes == 1 || c->elem_bytes == 2 || c->elem_bytes == 4) &&
+         (c->layout_src == AO_LAYOUT_HEAD_MAJOR || c->layout_src == AO_LAYOUT_TOKEN_MAJOR) &&
+         (c->layout_dst == AO_LAYOUT_HEAD_MAJOR || c->layout_dst == AO_LAYOUT_TOKEN_MAJOR) &&
+         c->num_seqs >= 0 && c->max_blocks_per_seq >= 0 && c->src_pool_blocks >= 0 &&
+         c->dst_pool_blocks >= 0;
+}
+
+// Element index inside one block.  h: head local to the rank, c: 0 = K, 1 = V,
+// t: token slot, x: position in the head vector, heads: heads per rank.
+//   header-centric  [Header, K/V, Token, d]   (Sec. 3.1, Improvement 1)
+//   token-first     [K/V, Token, Header, d]   (Sec. 3.1, base layout)
+int64_t block_index(int layout, int64_t h, int64_t c, int64_t t, int64_t x, int64_t heads,
+                    int64_t B, int64_t d) {
+  if (layout == AO_LAYOUT_HEAD_MAJOR) return ((h * 2 + c) * B + t) * d + x;
+  return ((c * B + t) * heads + h) * d + x;
+}
+
+template <typename E>
+int reshard_kv_t(const ao_kv* c, int k, int kp, int rp, const void* const* src_v,
+                 const int32_t* src_table, const int32_t* seq_lens, void* dst_v,
+                 int32_t* dst_table, int64_t* total_out) {
+  const int64_t S = c->num_seqs, W = c->max_blocks_per_seq, B = c->block_tokens, d = c->head_dim;
+  const int64_t Hs = c->n_kv_heads / k, Hd = c->n_kv_heads / kp;
+  const int64_t src_block = Hs * 2 * B * d, dst_block = Hd * 2 * B * d;
+
+  const E* src[64];
+  for (int s = 0; s < k; ++s) src[s] = static_cast<const E*>(src_v[s]);
+  for (int64_t hp = 0; hp < Hd; ++hp)  // every rank owning a needed head must be present
+    if (!src[((int64_t)rp * Hd + hp) / Hs]) return AO_ERR_ARG;
+
+  if (total_out) *total_out = 0;
+  for (int64_t i = 0; i < S * W; ++i) dst_table[i] = -1;
+
+  // step 1: blocks per sequence and the exclusive prefix sum, with the checks
+  bool overflow = false;
+  int64_t total = 0;
+  for (int64_t i = 0; i < S; ++i) {
+    const int64_t len = seq_lens[i];
+    if (len < 0) { overflow = true; continue; }
+    const int64_t nb = (len + B - 1) / B;
+    if (nb > W) overflow = true;
+    total += nb;
+  }
+  if (total > c->dst_pool_blocks) overflow = true;
+  if (overflow) return AO_ERR_OVERFLOW;
+
+  // step 2: the new table, sequence-major compact ids
+  int64_t base = 0;
+  for (int64_t i = 0; i < S; ++i) {
+    const int64_t nb = ((int64_t)seq_lens[i] + B - 1) / B;
+    for (int64_t j = 0; j < nb; ++j) dst_table[i * W + j] = (int32_t)(base + j);
+    base += nb;
+  }
+  if (total_out) *total_out = total;
+
+  // step 3: move the heads the target rank owns
+  E* dst = static_cast<E*>(dst_v);
+  bool bad_id = false;
+  for (int64_t l = 0; l < c->kv_layers; ++l) {
+    for (int64_t i = 0; i < S; ++i) {
+      const int64_t nb = ((int64_t)seq_lens[i] + B - 1) / B;
+      for (int64_t j = 0; j < nb; ++j) {
+        const int64_t sb = src_table[i * W + j];
+        const int64_t db = dst_table[i * W + j];
+        if (sb < 0 || sb >= c->src_pool_blocks) { bad_id = true; continue; }
+        for (int64_t t = 0; t < B; ++t)
+          for (int64_t kv = 0; kv < 2; ++kv)
+            for (int64_t hp = 0; hp < Hd; ++hp) {
+              const int64_t h = (int64_t)rp * Hd + hp;  // global KV head
+              const int64_t s = h / Hs;                 // source rank that owns it
+              const int64_t hs = h % Hs;                // its index on that rank
+              const E* from = src[s] + (l * c->src_pool_blocks + sb) * src_block;
+              E* to = dst + (l * c->dst_pool_blocks + db) * dst_block;
+              for (int64_t x = 0; x < d; ++x)
+                to[block_index(c->layout_dst, hp, kv, t, x, Hd, B, d)] =
+                    from[block_index(c->layout_src, hs, kv, t, x, Hs, B, d)];
+            }
+      }
+    }
+  }
+  return bad_id ? AO_ERR_BLOCK_ID : AO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t ao_shard_elems(const ao_model* m, int tp) {
+  if (!model_ok(m) || !tp_ok(m, tp)) return -1;
+  return geom(m, tp).layer_elems * m->n_layers;
+}
+
+int64_t ao_kv_block_elems(const ao_kv* c, int tp) {
+  if (!kv_ok(c) || !divides(tp, c->n_kv_heads)) return -1;
+  return (int64_t)(c->n_kv_heads / tp) * 2 * c->block_tokens * c->head_dim;
+}
+
+int ao_reshard_weights(const ao_model* m, int src_tp, int dst_tp, int dst_rank,
+                       const void* const* src_shards, void* dst) {
+  if (!model_ok(m) || src_tp > 64 || !tp_ok(m, src_tp) || !tp_ok(m, dst_tp) || dst_rank < 0 ||
+      dst_rank >= dst_tp || !src_shards || !dst)
+    return AO_ERR_ARG;
+  switch (m->elem_bytes) {
+    case 1: return reshard_weights_t<uint8_t>(m, src_tp, dst_tp, dst_rank, src_shards, dst);
+    case 2: return reshard_weights_t<uint16_t>(m, src_tp, dst_tp, dst_rank, src_shards, dst);
+    default: return reshard_weights_t<uint32_t>(m, src_tp, dst_tp, dst_rank, src_shards, dst);
+  }
+}
+
+int ao_reshard_kv(const ao_kv* c, int src_tp, int dst_tp, int dst_rank,
+                  const void* const* src_pools, const int32_t* src_table,
+                  const int32_t* seq_lens, void* dst_pool, int32_t* dst_table,
+                  int64_t* total_blocks_out) {
+  if (!kv_ok(c) || src_tp > 64 || !divides(src_tp, c->n_kv_heads) ||
+      !divides(dst_tp, c->n_kv_heads) || dst_rank < 0 || dst_rank >= dst_tp || !src_pools ||
+      !dst_pool || (c->num_seqs > 0 && (!seq_lens || !src_table || !dst_table)))
+    return AO_ERR_ARG;
+  switch (c->elem_bytes) {
+    case 1:
+      return reshard_kv_t<uint8_t>(c, src_tp, dst_tp, dst_rank, src_pools, src_table, seq_lens,
+                                   dst_pool, dst_table, total_blocks_out);
+    case 2:
+      return reshard_kv_t<uint16_t>(c, src_tp, dst_tp, dst_rank, src_pools, src_table, seq_lens,
+                                    dst_pool, dst_table, total_blocks_out);
+    default:
+      return reshard_kv_t<uint32_t>(c, src_tp, dst_tp, dst_rank, src_pools, src_table, seq_lens,
+                                    dst_pool, dst_table, total_blocks_out);
+  }
+}
+
+}  // extern "C"

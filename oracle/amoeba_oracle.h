@@ -1,0 +1,101 @@
+/*
+ * CPU oracle for runtime Tensor-Parallel (TP) transformation of one instance's
+ * state: TP=k shards -> target rank r' of TP=k'.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is the slow, single-threaded, per-element
+ * definition of the result.  It shares no code, header, table or helper with
+ * the HIP library; nothing in the product path may include, link or call it.
+ *
+ * What it follows (paper sections, restated):
+ *   - Sec. 2.2 (TP): attention heads are spread evenly over the workers, FFN
+ *     weights are cut in equal segments, one per worker.
+ *   - Sec. 3.2, Eq. (1) and the definition of U', D': up_proj is cut by
+ *     columns of the mathematical matrix U (FFN = f(I x U) x D), down_proj by
+ *     rows of D.  With tensors stored row-major as [out_features, in_features]
+ *     a column of U is a stored row of up_proj/gate_proj (contiguous cut) and
+ *     a row of D is a stored column of down_proj (strided cut).  q/k/v behave
+ *     like U, o_proj like D.
+ *   - Sec. 3.1, head-range rule: worker i of a TP group (1-based) owns heads
+ *     (H/TP)(i-1)+1 .. (H/TP)i, i.e. 0-based rank r owns [r*H/TP,(r+1)*H/TP).
+ *   - Sec. 3.1, KV layouts: "page-friendly" token-first block and the
+ *     header-centric block ordered [Block, Header, K/V, Token] with the head
+ *     dimension innermost.
+ *
+ * Every function below is pinned by tests/test_oracle_*.py (worked example of
+ * Sec. 3.1, brute-force enumeration, round trips, tiling of the unsharded
+ * tensors, torch cat/chunk/index_select special cases, Eq. (1)/(2) identity).
+ *
+ * All pointers are HOST pointers.  Elements are opaque (never interpreted).
+ */
+#ifndef AMOEBA_ORACLE_H
+#define AMOEBA_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { AO_LAYOUT_HEAD_MAJOR = 0, AO_LAYOUT_TOKEN_MAJOR = 1 };
+
+enum {
+  AO_OK = 0,
+  AO_ERR_ARG = 1,      /* bad shape / tp / rank / NULL pointer          */
+  AO_ERR_OVERFLOW = 2, /* tables or pool too small, negative length     */
+  AO_ERR_BLOCK_ID = 3  /* a source block id outside [0, src_pool_blocks) */
+};
+
+/* Decoder shape.  Unsharded tensors, row-major [out, in]:
+ *   Wq[n_q*d, hidden] Wk[n_kv*d, hidden] Wv[n_kv*d, hidden] Wo[hidden, n_q*d]
+ *   Wg[ffn, hidden]   Wu[ffn, hidden]    Wd[hidden, ffn]
+ * Rank r of TP=t stores per layer, packed in this order:
+ *   qkv_r     = [Wq rows of r's q heads; Wk rows of r's kv heads; Wv rows ...]
+ *   o_r       = Wo[:, columns of r's q heads]
+ *   gate_up_r = [Wg rows r*ffn/t ..; Wu rows r*ffn/t ..]
+ *   down_r    = Wd[:, columns r*ffn/t ..]
+ * and the layers follow each other without padding. */
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn_dim;
+  int32_t elem_bytes; /* 1, 2 or 4 */
+} ao_model;
+
+/* Paged KV cache.  A pool is [kv_layers][pool_blocks][block_elems(tp)];
+ * block tables are [num_seqs][max_blocks_per_seq] int32, -1 padded. */
+typedef struct {
+  int32_t kv_layers, n_kv_heads, head_dim, elem_bytes;
+  int32_t block_tokens;
+  int32_t layout_src, layout_dst;
+  int32_t num_seqs, max_blocks_per_seq;
+  int64_t src_pool_blocks, dst_pool_blocks;
+} ao_kv;
+
+/* Elements of one rank's weight shard at TP=tp, all layers; -1 if tp does not
+ * divide n_q_heads, n_kv_heads and ffn_dim. */
+int64_t ao_shard_elems(const ao_model* m, int tp);
+
+/* Elements of one KV block on a rank at TP=tp; -1 if tp does not divide heads. */
+int64_t ao_kv_block_elems(const ao_kv* c, int tp);
+
+/* dst <- rank dst_rank's shard at TP=dst_tp, gathered from the src_tp shards.
+ * src_shards: src_tp host pointers; ranks that own nothing of the target may
+ * be NULL.  dst must not overlap any source. */
+int ao_reshard_weights(const ao_model* m, int src_tp, int dst_tp, int dst_rank,
+                       const void* const* src_shards, void* dst);
+
+/* Sequence scan + table rewrite + block regroup by KV head.
+ *   nb_i = ceil(len_i / block_tokens); base_i = sum_{i'<i} nb_i';
+ *   dst_table[i][j] = base_i + j (j < nb_i) else -1;
+ *   every slot of every used block is copied for the heads dst_rank owns.
+ * One src table serves all src ranks.  On AO_ERR_OVERFLOW nothing is written
+ * to dst_pool and dst_table is all -1.  A block whose source id is out of
+ * range is skipped and AO_ERR_BLOCK_ID is returned after the rest is done.
+ * total_blocks_out (may be NULL) receives sum nb_i (0 on overflow). */
+int ao_reshard_kv(const ao_kv* c, int src_tp, int dst_tp, int dst_rank,
+                  const void* const* src_pools, const int32_t* src_table,
+                  const int32_t* seq_lens, void* dst_pool, int32_t* dst_table,
+                  int64_t* total_blocks_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
