@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the TP reshard hot path on one MI355X.
+
+One *step* is one pass of the whole hot path for one target rank: plan lookup is
+done once outside (it is host-only), then `amoeba_reshard_weights` over all
+layers and `amoeba_reshard_kv` (scan + table rewrite + block regroup) over the
+whole paged cache, with every input already resident in HBM.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b]
+
+prints ONE JSON line.  `value` is read+write GB/s over the algorithmic bytes
+(2 x bytes of the target shard and of the target KV blocks in use).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0  # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama7b")
+    ap.add_argument("--layout", default="hm-hm", choices=["hm-hm", "tm-tm", "tm-hm", "hm-tm"])
+    ap.add_argument("--kv-layers", type=int, default=0,
+                    help="KV layers resident per call (0 = all that fit the workload definition)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", default="", help="knob=value,... (AMOEBA_TUNE_* names, lower case)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU's share of the reshard on one GPU; "
+              "--gpus must be 1 (no collectives or multi-GPU sharding are part of it)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2509_19729_amd import binding as ab
+    from paper_2509_19729_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+    lay = {"hm": ab.KV_HEAD_MAJOR, "tm": ab.KV_TOKEN_MAJOR}
+    lay_s, lay_d = (lay[x] for x in args.layout.split("-"))
+
+    lens = wl.seq_lens(w)
+    table, src_pool_blocks = wl.block_placement(w, lens)
+    total_blocks = int(wl.blocks_per_seq(lens, w.block_tokens).sum())
+    dst_pool_blocks = total_blocks + 64
+    kv_layers = args.kv_layers or w.n_layers
+    if w.name == "llama13b" and not args.kv_layers:
+        kv_layers = 16  # the full 40-layer cache (src + dst) exceeds 288 GB; see the design doc
+    shape = ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim,
+                          elem_bytes=w.elem_bytes, kv_block_tokens=w.block_tokens,
+                          kv_layout_src=lay_s, kv_layout_dst=lay_d, kv_layers=kv_layers,
+                          num_seqs=w.num_seqs, max_blocks_per_seq=table.shape[1],
+                          src_pool_blocks=src_pool_blocks, dst_pool_blocks=dst_pool_blocks)
+    plan = ab.amoeba_plan(shape, w.src_tp, w.dst_tp, w.dst_rank)
+    knobs = {n[len("TUNE_"):].lower(): getattr(ab, n) for n in dir(ab) if n.startswith("TUNE_")}
+    for kv in filter(None, args.tune.split(",")):
+        name, val = kv.split("=")
+        ab.amoeba_plan_tune(plan, knobs[name], int(val))
+
+    # ---- synthetic state, generated on the device (values ~ N(0, 0.02), 16-bit) ----
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0xA30EBA00 + w.index)
+    fdt = torch.float16 if w.dtype == "fp16" else torch.bfloat16
+
+    def payload(n_elems):
+        t = torch.empty(n_elems, dtype=fdt, device="cuda")
+        step = 1 << 28
+        for a in range(0, n_elems, step):
+            t[a:a + step].normal_(0.0, 0.02, generator=gen)
+        return t
+
+    src_bytes, dst_bytes = ab.amoeba_plan_shard_bytes(plan, 0), ab.amoeba_plan_shard_bytes(plan, 1)
+    wmask, kmask = ab.amoeba_plan_src_rank_mask(plan), ab.amoeba_plan_kv_rank_mask(plan)
+    w_src = [payload(src_bytes // 2) if wmask >> r & 1 else None for r in range(w.src_tp)]
+    w_dst = torch.empty(dst_bytes // 2, dtype=fdt, device="cuda")
+    bb_s, bb_d = ab.amoeba_plan_kv_block_bytes(plan, 0), ab.amoeba_plan_kv_block_bytes(plan, 1)
+    kv_src = [payload(kv_layers * src_pool_blocks * bb_s // 2) if kmask >> r & 1 else None
+              for r in range(w.src_tp)]
+    kv_dst = torch.empty(kv_layers * dst_pool_blocks * bb_d // 2, dtype=fdt, device="cuda")
+    table_d = torch.from_numpy(table).cuda()
+    lens_d = torch.from_numpy(lens).cuda()
+    out_table = torch.empty_like(table_d)
+
+    w_alg = 2 * dst_bytes
+    kv_alg = 2 * total_blocks * bb_d * kv_layers
+    alg_bytes = w_alg + kv_alg
+
+    def step(ev=None):
+        ab.amoeba_reshard_weights(plan, w_src, w_dst)
+        if ev is not None:
+            ev[0].record()
+        ab.amoeba_reshard_kv(plan, kv_src, table_d, lens_d, kv_dst, out_table)
+        if ev is not None:
+            ev[1].record()
+
+    for _ in range(args.warmup):
+        step()
+    rc, n_blocks = ab.amoeba_kv_status(plan)
+    assert rc == ab.OK and n_blocks == total_blocks, (rc, n_blocks, ab.amoeba_last_error())
+
+    # events sit on torch's current stream, which is the stream the binding hands to the library
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    first.record()
+    for i in range(args.steps):
+        step(evs[i])
+    last.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kv_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps
+    dev_ms = first.elapsed_time(last) / args.steps
+    w_ms = dev_ms - kv_ms
+    value = alg_bytes / (ms_per_step * 1e-3) / 1e9
+
+    kv_gbps = kv_alg / (kv_ms * 1e-3) / 1e9
+    w_gbps = w_alg / (w_ms * 1e-3) / 1e9 if w_ms > 0 else None
+    out = {
+        "metric": "reshard throughput (read+write) of one TP transform, one target rank",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u16", "data": "synthetic",
+        "pct_of_hbm_peak": round(100.0 * value / PEAK_HBM_GBPS, 2),
+        "ms_per_tp_transform": round(ms_per_step, 4),
+        "config": {"workload": f"{w.name}: TP{w.src_tp}->TP{w.dst_tp} rank {w.dst_rank}, "
+                               f"{w.n_layers} layers, hidden {w.hidden}, {w.n_q_heads}q/"
+                               f"{w.n_kv_heads}kv heads, d {w.head_dim}, ffn {w.ffn_dim}, "
+                               f"{w.num_seqs} seqs / {int(lens.sum())} tokens / {total_blocks} "
+                               f"blocks of {w.block_tokens}, KV layers resident {kv_layers}",
+                   "kv_layout": args.layout, "weights_alg_bytes": w_alg, "kv_alg_bytes": kv_alg,
+                   "weights_ms": round(w_ms, 4), "weights_gbps": w_gbps and round(w_gbps, 1),
+                   "kv_ms": round(kv_ms, 4), "tune": args.tune},
+        "roofline": {"bound": "hbm", "kernel": "kv_regroup_kernel", "achieved": round(kv_gbps, 1),
+                     "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                     "frac": round(kv_gbps / PEAK_HBM_GBPS, 4), "traffic": None,
+                     "alg_bytes_per_launch": kv_alg, "avg_launch_ms": round(kv_ms, 4)},
+    }
+    traffic_file = os.path.join(ROOT, "profiles", f"traffic_{w.name}_{args.layout}.json")
+    if os.path.exists(traffic_file):
+        out["roofline"]["traffic"] = json.load(open(traffic_file)).get("kv_regroup_kernel_bytes")
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, lens, table, src_pool_blocks, dst_pool_blocks,
+                                           lay_s, lay_d)
+    plan.close()
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(w, lens, table, src_pool_blocks, dst_pool_blocks, lay_s, lay_d):
+    """The oracle, single thread, on a bounded sample of the same workload: a few real-shape
+    layers of weights and of the whole KV table."""
+    import numpy as np
+
+    import oracle
+    from paper_2509_19729_amd import workloads as wl
+
+    w_layers = max(1, min(w.n_layers, int(800e6 // max(1, _layer_bytes(w)))))
+    m = oracle.Model(w_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim)
+    n = oracle.shard_elems(m, w.src_tp)
+    src = [wl.random_bits(n, seed=11 + s) for s in range(w.src_tp)]
+    dst = np.zeros(oracle.shard_elems(m, w.dst_tp), dtype=np.uint16)
+    t0 = time.perf_counter()
+    st, dst = oracle.reshard_weights(m, w.src_tp, w.dst_tp, w.dst_rank, src, dst)
+    t_w = time.perf_counter() - t0
+    assert st == oracle.OK
+    bytes_w = 2 * dst.nbytes
+    del src, dst
+
+    kv = oracle.KV(kv_layers=1, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                   block_tokens=w.block_tokens, num_seqs=w.num_seqs,
+                   max_blocks_per_seq=table.shape[1], src_pool_blocks=src_pool_blocks,
+                   dst_pool_blocks=dst_pool_blocks, layout_src=lay_s, layout_dst=lay_d)
+    be_s, be_d = oracle.kv_block_elems(kv, w.src_tp), oracle.kv_block_elems(kv, w.dst_tp)
+    pools = [wl.random_bits(src_pool_blocks * be_s, seed=21 + s).reshape(1, src_pool_blocks, be_s)
+             for s in range(w.src_tp)]
+    dpool = np.zeros((1, dst_pool_blocks, be_d), dtype=np.uint16)
+    t0 = time.perf_counter()
+    st, _, total = oracle.reshard_kv(kv, w.src_tp, w.dst_tp, w.dst_rank, pools, table, lens, dpool)
+    t_kv = time.perf_counter() - t0
+    assert st == oracle.OK
+    bytes_kv = 2 * total * be_d * 2
+    gbps = (bytes_w + bytes_kv) / (t_w + t_kv) / 1e9
+    return {"value": round(gbps, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{w_layers} real-shape layers of weights ({bytes_w / 1e9:.2f} GB r+w, "
+                      f"{t_w:.2f} s) + 1 layer of the whole KV table ({bytes_kv / 1e9:.2f} GB r+w, "
+                      f"{t_kv:.2f} s); single thread, g++ -O2",
+            "host_cpus": os.cpu_count()}
+
+
+def _layer_bytes(w):
+    per = (2 * w.n_q_heads + 2 * w.n_kv_heads) * w.head_dim * w.hidden + 3 * w.hidden * w.ffn_dim
+    return per * w.elem_bytes // w.dst_tp
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,191 @@
+/*
+ * amoeba.h -- C ABI of the MI355X (gfx950) reshard library.
+ *
+ * Runtime Tensor-Parallel transformation of one serving instance, restated for
+ * one GPU: all source shards of TP = src_tp sit in this GPU's HBM and the
+ * library produces target rank dst_rank's share at TP = dst_tp.
+ *
+ *   weights : every decoder layer's fused QKV / O / gate_up / down tensors are
+ *             re-sliced by attention head and by FFN column/row partition
+ *             (paper Sec. 2.2; Sec. 3.2, Eq. (1) and the definition of U', D').
+ *   KV cache: every paged block is regrouped by KV head under a compacted,
+ *             rewritten block table (paper Sec. 3.1: the head-range rule "worker
+ *             W_i keeps heads (H/TP)(i-1)+1 .. (H/TP)i", the page-friendly
+ *             token-first block and the header-centric block
+ *             [Block, Header, K/V, Token]).
+ *
+ * Everything is an opaque move of 1-, 2- or 4-byte elements: no arithmetic on
+ * the payload.  All compute runs in HIP kernels; there is no CPU fallback.
+ *
+ * Storage convention (fixed by this library; the paper gives none).  Unsharded
+ * tensors are row-major [out_features, in_features]:
+ *     Wq[n_q*d, hidden] Wk[n_kv*d, hidden] Wv[n_kv*d, hidden] Wo[hidden, n_q*d]
+ *     Wg[ffn, hidden]   Wu[ffn, hidden]    Wd[hidden, ffn]
+ * Rank r of TP = t owns q heads [r*n_q/t, (r+1)*n_q/t), kv heads likewise and
+ * FFN units [r*ffn/t, (r+1)*ffn/t).  Its shard is, per layer and packed in this
+ * order with no padding, layers back to back:
+ *     qkv_r     [(n_q + 2 n_kv) d / t, hidden] = [Wq rows; Wk rows; Wv rows] of its heads
+ *     o_r       [hidden, n_q d / t]            = Wo[:, its q-head columns]
+ *     gate_up_r [2 ffn / t, hidden]            = [Wg rows; Wu rows] of its FFN units
+ *     down_r    [hidden, ffn / t]              = Wd[:, its FFN columns]
+ *
+ * A KV pool is [kv_layers][pool_blocks][block], one block holding
+ * kv_block_tokens tokens of the rank's n_kv/t heads, K and V, in one of
+ *     AMOEBA_KV_HEAD_MAJOR : [head][K/V][token][d]   (header-centric, Sec. 3.1 Improvement 1)
+ *     AMOEBA_KV_TOKEN_MAJOR: [K/V][token][head][d]   (token-first, Sec. 3.1 base layout)
+ * Block tables are int32 [num_seqs][max_blocks_per_seq], padded with -1.  One
+ * source table serves all source ranks (one instance, one scheduler).
+ *
+ * Threading: a plan is immutable after amoeba_plan() except for its small
+ * device workspace, which amoeba_reshard_kv() uses: two amoeba_reshard_kv()
+ * calls on the same plan must not overlap in time.  amoeba_reshard_weights()
+ * calls may overlap freely.
+ */
+#ifndef AMOEBA_H
+#define AMOEBA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AMOEBA_MAX_TP 16
+
+enum { AMOEBA_KV_HEAD_MAJOR = 0, AMOEBA_KV_TOKEN_MAJOR = 1 };
+
+enum {
+  AMOEBA_OK = 0,
+  AMOEBA_ERR_INVALID_ARG = 1, /* NULL plan / pointer, misaligned or aliased buffers      */
+  AMOEBA_ERR_HIP = 2,         /* a HIP call failed; text in amoeba_last_error()          */
+  AMOEBA_ERR_OVERFLOW = 3,    /* device found: negative length, table row or pool small  */
+  AMOEBA_ERR_BLOCK_ID = 4     /* device found: a source block id outside the source pool */
+};
+
+/* Tensor ids for amoeba_plan_tensor_info(). */
+enum {
+  AMOEBA_T_Q = 0, AMOEBA_T_K = 1, AMOEBA_T_V = 2, AMOEBA_T_O = 3,
+  AMOEBA_T_GATE = 4, AMOEBA_T_UP = 5, AMOEBA_T_DOWN = 6, AMOEBA_T_COUNT = 7
+};
+
+/* Knobs for amoeba_plan_tune(); 0 restores the built-in choice. */
+enum {
+  AMOEBA_TUNE_W_GRID = 0,    /* workgroups of the weight kernel (0: one per tile)       */
+  AMOEBA_TUNE_W_UNROLL = 1,  /* 16-byte vectors per lane per tile: 1, 2, 4 or 8          */
+  AMOEBA_TUNE_KV_GRID = 2,   /* workgroups of the KV regroup kernel                      */
+  AMOEBA_TUNE_KV_UNROLL = 3, /* vectors per lane per tile: 1, 2, 4 or 8                  */
+  AMOEBA_TUNE_KV_LAYERS = 4, /* layers one work item walks through                       */
+  AMOEBA_TUNE_NONTEMPORAL = 5, /* 1: streaming (nt) loads/stores, 2: plain               */
+  AMOEBA_TUNE_KV_STAGED = 6  /* 1: LDS-staged path for layout-converting regroup, 2: direct */
+};
+
+/* Caller-owned POD; amoeba_plan() copies it. */
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn_dim;
+  int32_t elem_bytes;      /* 1, 2 or 4; 2 = fp16/bf16, never interpreted                 */
+  int32_t kv_block_tokens; /* tokens per KV block on both sides (16 in the paper's engines) */
+  int32_t kv_layout_src, kv_layout_dst; /* AMOEBA_KV_*                                    */
+  int32_t kv_layers;       /* layers held by each KV pool passed to amoeba_reshard_kv     */
+  int32_t num_seqs, max_blocks_per_seq; /* block tables are [num_seqs][max_blocks_per_seq] */
+  int64_t src_pool_blocks, dst_pool_blocks; /* blocks per layer in each pool              */
+} amoeba_model_shape;
+
+typedef struct amoeba_plan_s amoeba_plan_t;
+
+/*
+ * Host-side planning (Sec. 3.2: partition boundaries are fixed per model and TP
+ * set, so they are computed once).  Builds the per-layer table of strided copy
+ * segments for the weights and the stride description of both KV layouts (the
+ * role of the paper's kv_stride_order(), Sec. 3.1), and allocates a device
+ * workspace of 4*(num_seqs + dst_pool_blocks + 8) bytes on the current device
+ * for the KV path (skipped, without error, when no GPU is present; then
+ * amoeba_reshard_kv() fails with AMOEBA_ERR_HIP).
+ * Returns NULL and sets amoeba_last_error() if: a size is not positive (num_seqs,
+ * max_blocks_per_seq and the pool sizes may be 0), dst_rank is outside
+ * [0, dst_tp), either TP degree exceeds AMOEBA_MAX_TP or does not divide
+ * n_q_heads, n_kv_heads and ffn_dim (fewer KV heads than ranks, i.e. head
+ * replication, is unsupported), n_q_heads is not a multiple of n_kv_heads,
+ * a layout or elem_bytes is unknown, or a pool has more than 2^31-1 blocks.
+ */
+amoeba_plan_t* amoeba_plan(const amoeba_model_shape* shape, int src_tp, int dst_tp, int dst_rank);
+
+/* Frees the plan and its device workspace.  NULL is ignored. */
+void amoeba_plan_destroy(amoeba_plan_t* plan);
+
+/*
+ * Weights (Sec. 2.2; Sec. 3.2 Eq. (1)): dst <- rank dst_rank's shard at dst_tp.
+ *   src_shards : HOST array of src_tp DEVICE pointers, entry s = rank s's shard
+ *                (amoeba_plan_shard_bytes(plan, 0) bytes).  Entries whose bit is
+ *                clear in amoeba_plan_src_rank_mask() are never read, may be NULL.
+ *   dst        : DEVICE buffer of amoeba_plan_shard_bytes(plan, 1) bytes; must not
+ *                overlap a source that is read (checked; AMOEBA_ERR_INVALID_ARG).
+ *   stream     : hipStream_t (NULL = default stream).
+ * Enqueues one kernel over all layers; does not synchronise, allocate or keep
+ * any pointer.  Any alignment works; 16-byte aligned buffers take the fast path.
+ */
+int amoeba_reshard_weights(const amoeba_plan_t* plan, const void* const* src_shards, void* dst,
+                           void* stream);
+
+/*
+ * KV cache (Sec. 3.1): scan sequence lengths, rewrite the block table, regroup
+ * every used block by KV head.
+ *   src_blocks       : HOST array of src_tp DEVICE pool pointers
+ *                      [kv_layers][src_pool_blocks][amoeba_plan_kv_block_bytes(plan,0)];
+ *                      ranks outside amoeba_plan_kv_rank_mask() may be NULL.
+ *   src_block_tables : DEVICE int32 [num_seqs][max_blocks_per_seq].
+ *   seq_lens         : DEVICE int32 [num_seqs], tokens per sequence.
+ *   dst_blocks       : DEVICE pool [kv_layers][dst_pool_blocks][amoeba_plan_kv_block_bytes(plan,1)].
+ *   dst_block_tables : DEVICE int32 [num_seqs][max_blocks_per_seq], fully overwritten:
+ *                      row i = base_i, base_i+1, .. for ceil(len_i/kv_block_tokens)
+ *                      entries, then -1; base = exclusive prefix sum in sequence order.
+ * Whole blocks move (all kv_block_tokens slots).  Enqueues three kernels on
+ * `stream`; no host synchronisation.  Conditions found on the device are reported
+ * by amoeba_kv_status(): on AMOEBA_ERR_OVERFLOW the pool is untouched and the
+ * table is all -1; a source block id outside [0, src_pool_blocks) skips that
+ * block (its destination block is left as it was) and yields AMOEBA_ERR_BLOCK_ID.
+ */
+int amoeba_reshard_kv(const amoeba_plan_t* plan, const void* const* src_blocks,
+                      const int32_t* src_block_tables, const int32_t* seq_lens, void* dst_blocks,
+                      int32_t* dst_block_tables, void* stream);
+
+/* Synchronises `stream`, then returns what the last amoeba_reshard_kv() on this
+ * plan found: AMOEBA_OK, AMOEBA_ERR_OVERFLOW or AMOEBA_ERR_BLOCK_ID (AMOEBA_ERR_HIP
+ * if the copy back fails).  total_blocks (may be NULL) receives sum_i nb_i. */
+int amoeba_kv_status(const amoeba_plan_t* plan, void* stream, int64_t* total_blocks);
+
+/* ---- queries (host only) ------------------------------------------------- */
+
+/* Bytes of one rank's weight shard, all layers.  side: 0 = source TP, 1 = target TP. */
+size_t amoeba_plan_shard_bytes(const amoeba_plan_t* plan, int side);
+/* Bytes of one KV block on one rank. */
+size_t amoeba_plan_kv_block_bytes(const amoeba_plan_t* plan, int side);
+/* Bit s set: source rank s holds weights the target rank needs. */
+uint32_t amoeba_plan_src_rank_mask(const amoeba_plan_t* plan);
+/* Bit s set: source rank s holds KV heads the target rank needs. */
+uint32_t amoeba_plan_kv_rank_mask(const amoeba_plan_t* plan);
+/* Where tensor `tensor` (AMOEBA_T_*) sits in a rank's per-layer shard: element offset
+ * from the layer start, rows, columns; *layer_elems = elements per layer.  Any out
+ * pointer may be NULL.  Returns AMOEBA_OK or AMOEBA_ERR_INVALID_ARG. */
+int amoeba_plan_tensor_info(const amoeba_plan_t* plan, int side, int tensor, int64_t* elem_off,
+                            int64_t* rows, int64_t* cols, int64_t* layer_elems);
+/* Strides, in elements, of (head, K/V, token, d) inside one block, and the block
+ * size: what an attention kernel needs to read either layout unchanged
+ * (Sec. 3.1, kv_stride_order()).  out[0..3] = strides, out[4] = block elements. */
+int amoeba_plan_kv_stride_order(const amoeba_plan_t* plan, int side, int64_t out[5]);
+/* Weight copy segments of one layer (for inspection and host-side tests).
+ * out = {src_rank, src_byte_off, src_pitch, dst_byte_off, dst_pitch, rows, run_bytes}. */
+int amoeba_plan_num_segments(const amoeba_plan_t* plan);
+int amoeba_plan_segment(const amoeba_plan_t* plan, int index, int64_t out[7]);
+
+/* Launch-shape knobs (AMOEBA_TUNE_*), for measurement sweeps.  Not thread-safe
+ * against concurrent reshard calls on the same plan. */
+int amoeba_plan_tune(amoeba_plan_t* plan, int knob, int value);
+
+/* Text of the calling thread's last error ("" if none). */
+const char* amoeba_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

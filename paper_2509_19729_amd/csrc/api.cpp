@@ -1,0 +1,212 @@
+// C ABI of the reshard library: argument checks, error text, plan lifetime.
+// The entry points and their contracts are documented in include/amoeba.h.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "../../include/amoeba.h"
+#include "launch.h"
+#include "plan.h"
+
+namespace {
+thread_local std::string g_last_error;
+}
+
+namespace amoeba {
+void set_error(const std::string& msg) { g_last_error = msg; }
+}  // namespace amoeba
+
+using amoeba::set_error;
+
+extern "C" {
+
+const char* amoeba_last_error(void) { return g_last_error.c_str(); }
+
+amoeba_plan_t* amoeba_plan(const amoeba_model_shape* shape, int src_tp, int dst_tp,
+                           int dst_rank) {
+  amoeba_plan_s* p = new (std::nothrow) amoeba_plan_s();
+  if (!p) { set_error("out of host memory"); return nullptr; }
+  std::string err;
+  if (!amoeba::build_plan(p, shape, src_tp, dst_tp, dst_rank, &err)) {
+    set_error("amoeba_plan: " + err);
+    delete p;
+    return nullptr;
+  }
+  p->device = -1;
+  p->n_cu = 0;
+  p->workspace = nullptr;
+  p->workspace_bytes = 0;
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) == hipSuccess && n_dev > 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess) {
+      int cu = 0;
+      if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+        p->n_cu = cu;
+      const size_t bytes = sizeof(int32_t) * (size_t(amoeba::kWsHeader) + size_t(p->shape.num_seqs) +
+                                              size_t(p->shape.dst_pool_blocks));
+      void* ws = nullptr;
+      const hipError_t rc = hipMalloc(&ws, bytes);
+      if (rc != hipSuccess) {
+        set_error(std::string("amoeba_plan: workspace allocation failed: ") +
+                  hipGetErrorString(rc));
+        delete p;
+        return nullptr;
+      }
+      p->device = dev;
+      p->workspace = static_cast<int32_t*>(ws);
+      p->workspace_bytes = bytes;
+    }
+  } else {
+    (void)hipGetLastError();  // no GPU: host-side planning only
+  }
+  g_last_error.clear();
+  return p;
+}
+
+void amoeba_plan_destroy(amoeba_plan_t* plan) {
+  if (!plan) return;
+  if (plan->workspace) (void)hipFree(plan->workspace);
+  delete plan;
+}
+
+int amoeba_reshard_weights(const amoeba_plan_t* plan, const void* const* src_shards, void* dst,
+                           void* stream) {
+  if (!plan || !src_shards || !dst) {
+    set_error("amoeba_reshard_weights: NULL plan, src_shards or dst");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  std::string err;
+  const int rc = amoeba::launch_reshard_weights(plan, src_shards, dst,
+                                                static_cast<hipStream_t>(stream), &err);
+  if (rc != AMOEBA_OK) set_error("amoeba_reshard_weights: " + err);
+  return rc;
+}
+
+int amoeba_reshard_kv(const amoeba_plan_t* plan, const void* const* src_blocks,
+                      const int32_t* src_block_tables, const int32_t* seq_lens, void* dst_blocks,
+                      int32_t* dst_block_tables, void* stream) {
+  if (!plan || !src_blocks) {
+    set_error("amoeba_reshard_kv: NULL plan or src_blocks");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  std::string err;
+  const int rc =
+      amoeba::launch_reshard_kv(plan, src_blocks, src_block_tables, seq_lens, dst_blocks,
+                                dst_block_tables, static_cast<hipStream_t>(stream), &err);
+  if (rc != AMOEBA_OK) set_error("amoeba_reshard_kv: " + err);
+  return rc;
+}
+
+int amoeba_kv_status(const amoeba_plan_t* plan, void* stream, int64_t* total_blocks) {
+  if (!plan || !plan->workspace) {
+    set_error("amoeba_kv_status: NULL plan or no device workspace");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  int32_t head[2] = {0, 0};
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t rc = hipMemcpyAsync(head, plan->workspace, sizeof(head), hipMemcpyDeviceToHost, st);
+  if (rc == hipSuccess) rc = hipStreamSynchronize(st);
+  if (rc != hipSuccess) {
+    set_error(std::string("amoeba_kv_status: ") + hipGetErrorString(rc));
+    return AMOEBA_ERR_HIP;
+  }
+  if (total_blocks) *total_blocks = head[amoeba::kWsTotal];
+  const int e = head[amoeba::kWsError];
+  if (e & (amoeba::kErrNegativeLen | amoeba::kErrRowTooShort | amoeba::kErrPoolTooSmall)) {
+    set_error(std::string("amoeba_kv_status: ") +
+              ((e & amoeba::kErrNegativeLen) ? "negative sequence length; " : "") +
+              ((e & amoeba::kErrRowTooShort) ? "a sequence needs more blocks than a table row holds; " : "") +
+              ((e & amoeba::kErrPoolTooSmall) ? "destination pool too small; " : ""));
+    return AMOEBA_ERR_OVERFLOW;
+  }
+  if (e & amoeba::kErrBlockId) {
+    set_error("amoeba_kv_status: a source block id lies outside the source pool");
+    return AMOEBA_ERR_BLOCK_ID;
+  }
+  return AMOEBA_OK;
+}
+
+size_t amoeba_plan_shard_bytes(const amoeba_plan_t* plan, int side) {
+  if (!plan) return 0;
+  const amoeba::ShardLayout& L = side ? plan->dst_layout : plan->src_layout;
+  return size_t(L.layer_elems) * size_t(plan->shape.elem_bytes) * size_t(plan->shape.n_layers);
+}
+
+size_t amoeba_plan_kv_block_bytes(const amoeba_plan_t* plan, int side) {
+  if (!plan) return 0;
+  return size_t(side ? plan->block_bytes_dst : plan->block_bytes_src);
+}
+
+uint32_t amoeba_plan_src_rank_mask(const amoeba_plan_t* plan) {
+  return plan ? plan->weight_rank_mask : 0;
+}
+
+uint32_t amoeba_plan_kv_rank_mask(const amoeba_plan_t* plan) {
+  return plan ? plan->kv_rank_mask : 0;
+}
+
+int amoeba_plan_tensor_info(const amoeba_plan_t* plan, int side, int tensor, int64_t* elem_off,
+                            int64_t* rows, int64_t* cols, int64_t* layer_elems) {
+  if (!plan || tensor < 0 || tensor >= AMOEBA_T_COUNT || (side != 0 && side != 1)) {
+    set_error("amoeba_plan_tensor_info: bad plan, side or tensor id");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  const amoeba::ShardLayout& L = side ? plan->dst_layout : plan->src_layout;
+  if (elem_off) *elem_off = L.off[tensor];
+  if (rows) *rows = L.rows[tensor];
+  if (cols) *cols = L.cols[tensor];
+  if (layer_elems) *layer_elems = L.layer_elems;
+  return AMOEBA_OK;
+}
+
+int amoeba_plan_kv_stride_order(const amoeba_plan_t* plan, int side, int64_t out[5]) {
+  if (!plan || !out || (side != 0 && side != 1)) {
+    set_error("amoeba_plan_kv_stride_order: bad plan, side or out");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  const int64_t heads = side ? plan->heads_dst : plan->heads_src;
+  const int layout = side ? plan->shape.kv_layout_dst : plan->shape.kv_layout_src;
+  const int64_t B = plan->shape.kv_block_tokens, d = plan->shape.head_dim;
+  if (layout == AMOEBA_KV_HEAD_MAJOR) {  // [head][K/V][token][d]
+    out[0] = 2 * B * d; out[1] = B * d; out[2] = d; out[3] = 1;
+  } else {                               // [K/V][token][head][d]
+    out[0] = d; out[1] = B * heads * d; out[2] = heads * d; out[3] = 1;
+  }
+  out[4] = heads * 2 * B * d;
+  return AMOEBA_OK;
+}
+
+int amoeba_plan_num_segments(const amoeba_plan_t* plan) {
+  return plan ? int(plan->segments.size()) : 0;
+}
+
+int amoeba_plan_segment(const amoeba_plan_t* plan, int index, int64_t out[7]) {
+  if (!plan || !out || index < 0 || index >= int(plan->segments.size())) {
+    set_error("amoeba_plan_segment: bad plan, index or out");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  const amoeba::Segment& g = plan->segments[size_t(index)];
+  out[0] = g.src_rank; out[1] = g.src_off; out[2] = g.src_pitch; out[3] = g.dst_off;
+  out[4] = g.dst_pitch; out[5] = g.rows; out[6] = g.run;
+  return AMOEBA_OK;
+}
+
+int amoeba_plan_tune(amoeba_plan_t* plan, int knob, int value) {
+  if (!plan || value < 0) { set_error("amoeba_plan_tune: bad plan or value"); return AMOEBA_ERR_INVALID_ARG; }
+  switch (knob) {
+    case AMOEBA_TUNE_W_GRID: plan->tune.w_grid = value; break;
+    case AMOEBA_TUNE_W_UNROLL: plan->tune.w_unroll = value; break;
+    case AMOEBA_TUNE_KV_GRID: plan->tune.kv_grid = value; break;
+    case AMOEBA_TUNE_KV_UNROLL: plan->tune.kv_unroll = value; break;
+    case AMOEBA_TUNE_KV_LAYERS: plan->tune.kv_layers = value; break;
+    case AMOEBA_TUNE_NONTEMPORAL: plan->tune.nontemporal = value; break;
+    case AMOEBA_TUNE_KV_STAGED: plan->tune.kv_staged = value; break;
+    default: set_error("amoeba_plan_tune: unknown knob"); return AMOEBA_ERR_INVALID_ARG;
+  }
+  return AMOEBA_OK;
+}
+
+}  // extern "C"

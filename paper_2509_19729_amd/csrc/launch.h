@@ -1,0 +1,22 @@
+// Internal: host launchers of the two reshard paths (defined in the .hip files).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <string>
+
+struct amoeba_plan_s;
+
+namespace amoeba {
+
+// Workspace header (int32 words) shared by the KV kernels and the status call.
+enum { kWsTotal = 0, kWsError = 1, kWsHeader = 8 };
+enum { kErrNegativeLen = 1, kErrRowTooShort = 2, kErrPoolTooSmall = 4, kErrBlockId = 8 };
+
+int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards, void* dst,
+                           hipStream_t stream, std::string* err);
+
+int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
+                      const int32_t* src_block_tables, const int32_t* seq_lens, void* dst_blocks,
+                      int32_t* dst_block_tables, hipStream_t stream, std::string* err);
+
+}  // namespace amoeba

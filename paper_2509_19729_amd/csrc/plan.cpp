@@ -1,0 +1,131 @@
+// Host-side planning: shard geometry, copy segments, KV block geometry.
+//
+// The partition follows the paper's statement of tensor parallelism (Sec. 2.2:
+// heads and FFN segments spread evenly over the workers) and of the FFN cut
+// (Sec. 3.2, Eq. (1): up_proj by columns of U, down_proj by rows of D).  With
+// [out, in] row-major storage the q/k/v/gate/up cuts fall on stored rows
+// (contiguous ranges) and the o/down cuts on stored columns (strided ranges).
+// Ownership is by contiguous index ranges (Sec. 3.1 head-range rule), so the
+// target rank's range of each partitioned axis is intersected with every source
+// rank's range; each non-empty intersection is one copy segment.
+#include "plan.h"
+
+#include <algorithm>
+
+namespace amoeba {
+
+namespace {
+
+ShardLayout shard_layout(const amoeba_model_shape& s, int tp) {
+  ShardLayout L;
+  const int64_t H = s.hidden, d = s.head_dim;
+  const int64_t q = int64_t(s.n_q_heads) * d / tp, kv = int64_t(s.n_kv_heads) * d / tp,
+                f = int64_t(s.ffn_dim) / tp;
+  const int64_t rows[AMOEBA_T_COUNT] = {q, kv, kv, H, f, f, H};
+  const int64_t cols[AMOEBA_T_COUNT] = {H, H, H, q, H, H, f};
+  int64_t at = 0;
+  for (int t = 0; t < AMOEBA_T_COUNT; ++t) {
+    L.off[t] = at;
+    L.rows[t] = rows[t];
+    L.cols[t] = cols[t];
+    at += rows[t] * cols[t];
+  }
+  L.layer_elems = at;
+  return L;
+}
+
+bool fail(std::string* err, const std::string& msg) {
+  if (err) *err = msg;
+  return false;
+}
+
+}  // namespace
+
+bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp, int rp,
+                std::string* err) {
+  if (!shape) return fail(err, "shape is NULL");
+  const amoeba_model_shape& s = *shape;
+  if (s.n_layers <= 0 || s.hidden <= 0 || s.n_q_heads <= 0 || s.n_kv_heads <= 0 ||
+      s.head_dim <= 0 || s.ffn_dim <= 0 || s.kv_block_tokens <= 0 || s.kv_layers <= 0)
+    return fail(err, "model sizes must be positive");
+  if (s.elem_bytes != 1 && s.elem_bytes != 2 && s.elem_bytes != 4)
+    return fail(err, "elem_bytes must be 1, 2 or 4");
+  if (s.n_q_heads % s.n_kv_heads) return fail(err, "n_q_heads must be a multiple of n_kv_heads");
+  for (int lay : {s.kv_layout_src, s.kv_layout_dst})
+    if (lay != AMOEBA_KV_HEAD_MAJOR && lay != AMOEBA_KV_TOKEN_MAJOR)
+      return fail(err, "unknown KV layout");
+  if (s.num_seqs < 0 || s.max_blocks_per_seq < 0 || s.src_pool_blocks < 0 ||
+      s.dst_pool_blocks < 0)
+    return fail(err, "negative table or pool size");
+  if (s.src_pool_blocks > INT32_MAX || s.dst_pool_blocks > INT32_MAX)
+    return fail(err, "a pool has more than 2^31-1 blocks (block ids are int32)");
+  for (int tp : {k, kp}) {
+    if (tp < 1 || tp > AMOEBA_MAX_TP) return fail(err, "TP degree outside [1, 16]");
+    if (s.n_q_heads % tp || s.n_kv_heads % tp || s.ffn_dim % tp)
+      return fail(err, "TP degree must divide n_q_heads, n_kv_heads and ffn_dim");
+  }
+  if (rp < 0 || rp >= kp) return fail(err, "dst_rank outside [0, dst_tp)");
+
+  p->shape = s;
+  p->k = k;
+  p->kp = kp;
+  p->rp = rp;
+  p->src_layout = shard_layout(s, k);
+  p->dst_layout = shard_layout(s, kp);
+  p->segments.clear();
+  p->weight_rank_mask = 0;
+
+  const int64_t e = s.elem_bytes;
+  const int64_t d = s.head_dim;
+  // extent of the partitioned axis of each tensor in the unsharded model
+  const int64_t axis[AMOEBA_T_COUNT] = {int64_t(s.n_q_heads) * d, int64_t(s.n_kv_heads) * d,
+                                        int64_t(s.n_kv_heads) * d, int64_t(s.n_q_heads) * d,
+                                        s.ffn_dim,                 s.ffn_dim,
+                                        s.ffn_dim};
+  for (int t = 0; t < AMOEBA_T_COUNT; ++t) {
+    const bool cut_on_rows = (t != AMOEBA_T_O && t != AMOEBA_T_DOWN);
+    const int64_t N = axis[t], per_src = N / k, per_dst = N / kp;
+    const int64_t want_lo = rp * per_dst, want_hi = want_lo + per_dst;
+    for (int r = 0; r < k; ++r) {
+      const int64_t lo = std::max(want_lo, r * per_src), hi = std::min(want_hi, (r + 1) * per_src);
+      if (lo >= hi) continue;
+      Segment g;
+      g.src_rank = r;
+      if (cut_on_rows) {
+        const int64_t width = p->src_layout.cols[t];  // == hidden on both sides
+        g.src_off = (p->src_layout.off[t] + (lo - r * per_src) * width) * e;
+        g.dst_off = (p->dst_layout.off[t] + (lo - want_lo) * width) * e;
+        g.rows = 1;
+        g.run = (hi - lo) * width * e;
+        g.src_pitch = g.dst_pitch = g.run;
+      } else {
+        g.src_off = (p->src_layout.off[t] + (lo - r * per_src)) * e;
+        g.dst_off = (p->dst_layout.off[t] + (lo - want_lo)) * e;
+        g.src_pitch = per_src * e;
+        g.dst_pitch = per_dst * e;
+        g.rows = p->src_layout.rows[t];  // == hidden on both sides
+        g.run = (hi - lo) * e;
+        if (g.run == g.src_pitch && g.run == g.dst_pitch) {  // whole rows: one contiguous range
+          g.run *= g.rows;
+          g.rows = 1;
+          g.src_pitch = g.dst_pitch = g.run;
+        }
+      }
+      p->segments.push_back(g);
+      p->weight_rank_mask |= 1u << r;
+    }
+  }
+
+  // KV: contiguous head ranges again (Sec. 3.1); whole heads move, so only the
+  // owning ranks are recorded here and the per-head mapping is done in the kernel.
+  p->heads_src = s.n_kv_heads / k;
+  p->heads_dst = s.n_kv_heads / kp;
+  p->block_bytes_src = p->heads_src * 2 * s.kv_block_tokens * d * e;
+  p->block_bytes_dst = p->heads_dst * 2 * s.kv_block_tokens * d * e;
+  p->kv_rank_mask = 0;
+  for (int64_t h = rp * p->heads_dst; h < (rp + 1) * p->heads_dst; ++h)
+    p->kv_rank_mask |= 1u << (h / p->heads_src);
+  return true;
+}
+
+}  // namespace amoeba

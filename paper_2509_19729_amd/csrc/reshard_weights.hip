@@ -1,0 +1,198 @@
+// Weight reshard kernel: one launch gathers the target rank's shard for all layers.
+//
+// What it computes (paper Sec. 2.2 and Sec. 3.2 Eq. (1)): the target rank's slice
+// of q/k/v/gate/up (cut along stored rows) and of o/down (cut along stored
+// columns), taken from whichever source ranks hold it.  The host planner has
+// already expressed that as a short per-layer table of strided byte rectangles;
+// this kernel is a table-driven streaming gather.
+//
+// Mapping to the machine.  The work is HBM-bound (every byte is read once and
+// written once), so: each lane moves 16 bytes per access, a workgroup of 256
+// lanes owns a tile of UNROLL x 4 KiB that is contiguous in the destination,
+// all loads of a tile are issued before its first store, and accesses carry the
+// non-temporal hint because nothing is reused.  Tiles are numbered in
+// destination order (layer, segment, position) so that the workgroups in flight
+// at any time sweep one contiguous window of the destination.  Within a strided
+// rectangle the lane's vector index n is split into (row, column) with a
+// multiply-high division by the row length.
+#include <algorithm>
+#include <string>
+
+#include "device_common.h"
+#include "launch.h"
+#include "plan.h"
+
+namespace amoeba {
+
+constexpr int kMaxSegs = 64;  // segments per launch (kernel arguments are limited to 4 KiB)
+
+struct WSeg {
+  const char* src;      // layer 0 address of the segment's first vector
+  int64_t dst_off;      // byte offset of its first vector in the target shard, layer 0
+  uint32_t src_pitch;   // bytes between rows, source side
+  uint32_t dst_pitch;   // bytes between rows, target side
+  uint32_t total_vecs;  // rows * row_vecs
+  FastDiv row_vecs;     // vectors per row
+};
+
+struct WArgs {
+  WSeg seg[kMaxSegs];
+  uint32_t tile_begin[kMaxSegs];  // first tile of each segment within a layer
+  char* dst;
+  int64_t src_layer_stride, dst_layer_stride;  // bytes
+  uint32_t n_seg;
+  uint32_t total_tiles;  // tiles_per_layer * n_layers
+  FastDiv tiles_per_layer;
+};
+
+template <int VEC, int UNROLL, bool NT>
+__global__ void __launch_bounds__(kThreads) reshard_weights_kernel(const WArgs a) {
+  using V = typename VecOf<VEC>::type;
+  constexpr uint32_t kTileVecs = kThreads * UNROLL;
+  const uint32_t tid = threadIdx.x;
+
+  for (uint32_t w = blockIdx.x; w < a.total_tiles; w += gridDim.x) {
+    const uint32_t layer = fd_div(w, a.tiles_per_layer);
+    const uint32_t t = w - layer * a.tiles_per_layer.d;
+    // last segment whose first tile is <= t (uniform across the workgroup)
+    uint32_t lo = 0, hi = a.n_seg;
+    while (hi - lo > 1) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (a.tile_begin[mid] <= t) lo = mid; else hi = mid;
+    }
+    const WSeg& s = a.seg[lo];
+    const char* src = s.src + int64_t(layer) * a.src_layer_stride;
+    char* dst = a.dst + s.dst_off + int64_t(layer) * a.dst_layer_stride;
+    const uint32_t n0 = (t - a.tile_begin[lo]) * kTileVecs + tid;
+
+    V val[UNROLL];
+    uint64_t doff[UNROLL];
+    bool live[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const uint32_t n = n0 + u * kThreads;
+      live[u] = n < s.total_vecs;
+      const uint32_t row = fd_div(n, s.row_vecs);
+      const uint32_t col = n - row * s.row_vecs.d;
+      const uint64_t soff = uint64_t(row) * s.src_pitch + uint64_t(col) * VEC;
+      doff[u] = uint64_t(row) * s.dst_pitch + uint64_t(col) * VEC;
+      if (live[u]) val[u] = ld<NT, V>(src + soff);
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+      if (live[u]) st<NT, V>(dst + doff[u], val[u]);
+  }
+}
+
+namespace {
+
+template <int VEC, int UNROLL>
+void launch_one(bool nt, dim3 grid, hipStream_t stream, const WArgs& a) {
+  if (nt)
+    hipLaunchKernelGGL((reshard_weights_kernel<VEC, UNROLL, true>), grid, dim3(kThreads), 0,
+                       stream, a);
+  else
+    hipLaunchKernelGGL((reshard_weights_kernel<VEC, UNROLL, false>), grid, dim3(kThreads), 0,
+                       stream, a);
+}
+
+void dispatch(int vec, int unroll, bool nt, dim3 grid, hipStream_t stream, const WArgs& a) {
+  if (vec == 16) {
+    switch (unroll) {
+      case 1: launch_one<16, 1>(nt, grid, stream, a); break;
+      case 2: launch_one<16, 2>(nt, grid, stream, a); break;
+      case 8: launch_one<16, 8>(nt, grid, stream, a); break;
+      default: launch_one<16, 4>(nt, grid, stream, a); break;
+    }
+  } else if (vec == 8) {
+    launch_one<8, 4>(nt, grid, stream, a);
+  } else if (vec == 4) {
+    launch_one<4, 4>(nt, grid, stream, a);
+  } else if (vec == 2) {
+    launch_one<2, 4>(nt, grid, stream, a);
+  } else {
+    launch_one<1, 4>(nt, grid, stream, a);
+  }
+}
+
+}  // namespace
+
+int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards, void* dst,
+                           hipStream_t stream, std::string* err) {
+  const int64_t e = p->shape.elem_bytes;
+  const int64_t src_layer = p->src_layout.layer_elems * e, dst_layer = p->dst_layout.layer_elems * e;
+  const uint64_t src_bytes = uint64_t(src_layer) * p->shape.n_layers,
+                 dst_bytes = uint64_t(dst_layer) * p->shape.n_layers;
+
+  // widest access every address of this call is aligned to
+  uint64_t bits = uint64_t(src_layer) | uint64_t(dst_layer) | reinterpret_cast<uint64_t>(dst);
+  for (const Segment& g : p->segments) {
+    bits |= uint64_t(g.src_off) | uint64_t(g.dst_off) | uint64_t(g.run);
+    if (g.rows > 1) bits |= uint64_t(g.src_pitch) | uint64_t(g.dst_pitch);
+  }
+  const uint64_t d0 = reinterpret_cast<uint64_t>(dst);
+  for (int r = 0; r < p->k; ++r) {
+    if (!(p->weight_rank_mask >> r & 1)) continue;
+    const uint64_t s0 = reinterpret_cast<uint64_t>(src_shards[r]);
+    if (!s0) { *err = "a needed source shard pointer is NULL"; return AMOEBA_ERR_INVALID_ARG; }
+    if (s0 < d0 + dst_bytes && d0 < s0 + src_bytes) {
+      *err = "dst overlaps a source shard (the reshard is out of place)";
+      return AMOEBA_ERR_INVALID_ARG;
+    }
+    bits |= s0;
+  }
+  const int vec = common_alignment(bits);
+  int unroll = p->tune.w_unroll;
+  if (vec != 16 || (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8)) unroll = 4;
+  const bool nt = p->tune.nontemporal != 2;
+  const uint64_t tile_vecs = uint64_t(kThreads) * unroll;
+
+  const size_t n = p->segments.size();
+  for (size_t first = 0; first < n; first += kMaxSegs) {
+    WArgs a;
+    a.dst = static_cast<char*>(dst);
+    a.src_layer_stride = src_layer;
+    a.dst_layer_stride = dst_layer;
+    a.n_seg = uint32_t(std::min<size_t>(kMaxSegs, n - first));
+    uint64_t tiles = 0;
+    for (uint32_t i = 0; i < a.n_seg; ++i) {
+      const Segment& g = p->segments[first + i];
+      const uint64_t row_vecs = uint64_t(g.run) / vec, total = row_vecs * uint64_t(g.rows);
+      const bool strided = g.rows > 1;
+      if (total >= (uint64_t(1) << 32) - 65536 ||
+          (strided && (uint64_t(g.src_pitch) >= (uint64_t(1) << 32) ||
+                       uint64_t(g.dst_pitch) >= (uint64_t(1) << 32)))) {
+        *err = "a weight segment is too large for 32-bit tile indexing";
+        return AMOEBA_ERR_INVALID_ARG;
+      }
+      WSeg& s = a.seg[i];
+      s.src = static_cast<const char*>(src_shards[g.src_rank]) + g.src_off;
+      s.dst_off = g.dst_off;
+      s.src_pitch = strided ? uint32_t(g.src_pitch) : 0;  // a single row never uses its pitch
+      s.dst_pitch = strided ? uint32_t(g.dst_pitch) : 0;
+      s.total_vecs = uint32_t(total);
+      s.row_vecs = make_fastdiv(uint32_t(row_vecs));
+      a.tile_begin[i] = uint32_t(tiles);
+      tiles += (total + tile_vecs - 1) / tile_vecs;
+    }
+    const uint64_t total_tiles = tiles * uint64_t(p->shape.n_layers);
+    if (total_tiles >= (uint64_t(1) << 31)) {
+      *err = "too many tiles for one launch";
+      return AMOEBA_ERR_INVALID_ARG;
+    }
+    if (total_tiles == 0) continue;
+    a.total_tiles = uint32_t(total_tiles);
+    a.tiles_per_layer = make_fastdiv(uint32_t(tiles));
+    uint64_t grid = total_tiles;
+    if (p->tune.w_grid > 0) grid = std::min<uint64_t>(grid, uint64_t(p->tune.w_grid));
+    dispatch(vec, unroll, nt, dim3(uint32_t(grid)), stream, a);
+    const hipError_t rc = hipGetLastError();
+    if (rc != hipSuccess) {
+      *err = std::string("weight kernel launch failed: ") + hipGetErrorString(rc);
+      return AMOEBA_ERR_HIP;
+    }
+  }
+  return AMOEBA_OK;
+}
+
+}  // namespace amoeba

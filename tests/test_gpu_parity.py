@@ -1,0 +1,319 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle,
+bit for bit, on the same seeded inputs.  Sizes span several tiles, ragged tails,
+every vector width, every layout pair and the degenerate cases."""
+import dataclasses
+import itertools
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import gpu_reshard_kv, gpu_reshard_weights, sentinel_elem
+from paper_2509_19729_amd import binding as ab
+from paper_2509_19729_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+HM, TM = ab.KV_HEAD_MAJOR, ab.KV_TOKEN_MAJOR
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print(f"\n[gpu-case] {request.node.nodeid}", flush=True)
+    sys.stdout.flush()
+    yield
+
+
+def rand_shards(m, tp, seed):
+    n = oracle.shard_elems(m, tp)
+    return [wl.random_bits(n, seed=seed + s, elem_bytes=m.elem_bytes) for s in range(tp)]
+
+
+def check_weights(m, k, kp, rp, src, tune=None):
+    got, intact = gpu_reshard_weights(m, k, kp, rp, src, tune=tune)
+    st, want = oracle.reshard_weights(m, k, kp, rp, src)
+    assert st == oracle.OK
+    assert intact, "bytes outside the destination shard were written"
+    np.testing.assert_array_equal(got, want)
+
+
+# ------------------------------------------------------------------ weights
+SMALL = oracle.Model(n_layers=2, hidden=48, n_q_heads=24, n_kv_heads=12, head_dim=4, ffn_dim=96)
+
+
+@pytest.mark.parametrize("k,kp", [(1, 2), (2, 1), (4, 2), (2, 4), (1, 4), (4, 1), (2, 3), (3, 2),
+                                  (6, 4), (2, 2), (12, 1), (1, 12)])
+def test_weights_small_all_ranks(k, kp):
+    src = rand_shards(SMALL, k, seed=k * 31 + kp)
+    for rp in range(kp):
+        check_weights(SMALL, k, kp, rp, src)
+
+
+@pytest.mark.parametrize("elem_bytes", [1, 2, 4])
+@pytest.mark.parametrize("hidden,d,ffn", [(64, 8, 264),     # 16-byte vectors at 2-byte elements
+                                          (36, 4, 100),     # 8-byte runs
+                                          (34, 2, 98),      # 4-byte runs
+                                          (33, 1, 97)])     # 2-byte runs (1 at elem_bytes 1)
+def test_weights_every_vector_width(elem_bytes, hidden, d, ffn):
+    m = oracle.Model(n_layers=3, hidden=hidden, n_q_heads=4, n_kv_heads=2, head_dim=d,
+                     ffn_dim=ffn * 2, elem_bytes=elem_bytes)
+    for k, kp in [(1, 2), (2, 1)]:
+        src = rand_shards(m, k, seed=elem_bytes)
+        for rp in range(kp):
+            check_weights(m, k, kp, rp, src)
+
+
+@pytest.mark.parametrize("unroll", [1, 2, 4, 8])
+@pytest.mark.parametrize("grid", [0, 7, 300])
+def test_weights_several_tiles_and_ragged_tails(unroll, grid):
+    """Segments of 2.6 tiles and more, rows that are not a multiple of the tile, both
+    the one-workgroup-per-tile launch and the grid-stride launch."""
+    m = oracle.Model(n_layers=3, hidden=520, n_q_heads=8, n_kv_heads=4, head_dim=40, ffn_dim=1208)
+    tune = {ab.TUNE_W_UNROLL: unroll, ab.TUNE_W_GRID: grid}
+    for k, kp, rp in [(4, 2, 1), (1, 4, 3), (2, 1, 0)]:
+        check_weights(m, k, kp, rp, rand_shards(m, k, seed=unroll), tune=tune)
+
+
+def test_weights_plain_loads_variant():
+    m = oracle.Model(n_layers=2, hidden=256, n_q_heads=8, n_kv_heads=8, head_dim=32, ffn_dim=1024)
+    check_weights(m, 2, 4, 3, rand_shards(m, 2, seed=5), tune={ab.TUNE_NONTEMPORAL: 2})
+
+
+def test_weights_misaligned_buffers_fall_back_to_narrow_vectors():
+    m = oracle.Model(n_layers=2, hidden=64, n_q_heads=8, n_kv_heads=8, head_dim=8, ffn_dim=256)
+    k, kp, rp = 2, 1, 0
+    src = rand_shards(m, k, seed=9)
+    plan = ab.amoeba_plan(ab.ModelShape(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads,
+                                        m.head_dim, m.ffn_dim), k, kp, rp)
+    n_dst = ab.amoeba_plan_shard_bytes(plan, 1)
+    st, want = oracle.reshard_weights(m, k, kp, rp, src)
+    for shift in (2, 4, 8):
+        dev = []
+        for a in src:       # place each source `shift` bytes past an aligned address
+            t = torch.zeros(a.nbytes + 64, dtype=torch.uint8, device="cuda")
+            t[shift:shift + a.nbytes] = torch.from_numpy(a.view(np.uint8)).cuda()
+            dev.append(t[shift:shift + a.nbytes])
+        out = torch.zeros(n_dst + 64, dtype=torch.uint8, device="cuda")
+        ab.amoeba_reshard_weights(plan, dev, out[shift:shift + n_dst])
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        np.testing.assert_array_equal(got[shift:shift + n_dst].view(np.uint16), want)
+        assert (got[:shift] == 0).all() and (got[shift + n_dst:] == 0).all()
+
+
+def test_weights_overlapping_destination_is_refused():
+    m = SMALL
+    plan = ab.amoeba_plan(ab.ModelShape(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads,
+                                        m.head_dim, m.ffn_dim), 1, 1, 0)
+    n = ab.amoeba_plan_shard_bytes(plan, 0)
+    buf = torch.zeros(2 * n, dtype=torch.uint8, device="cuda")
+    rc = ab.amoeba_reshard_weights(plan, [buf[:n]], buf[n // 2:n // 2 + n], check=False)
+    assert rc == ab.ERR_INVALID_ARG and "overlap" in ab.amoeba_last_error()
+    rc = ab.amoeba_reshard_weights(plan, [None], buf[n:], check=False)
+    assert rc == ab.ERR_INVALID_ARG
+
+
+def test_weights_tiny_config_all_target_ranks():
+    w = wl.WORKLOADS["tiny"]
+    m = oracle.Model(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim)
+    n = oracle.shard_elems(m, w.src_tp)
+    src = [wl.payload16(n, seed=0xA30EBA00 + w.index + s, dtype=w.dtype) for s in range(w.src_tp)]
+    for rp in range(w.dst_tp):
+        check_weights(m, w.src_tp, w.dst_tp, rp, src)
+
+
+@pytest.mark.parametrize("name", ["llama7b", "llama13b", "gqa70b", "long8b"])
+def test_weights_real_layer_shapes(name):
+    """Three real-shape layers of each benchmark model (the full-depth launch is checked
+    in test_gpu_fullsize.py)."""
+    w = wl.WORKLOADS[name]
+    m = oracle.Model(3, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim)
+    plan = ab.amoeba_plan(ab.ModelShape(3, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim,
+                                        w.ffn_dim), w.src_tp, w.dst_tp, w.dst_rank)
+    mask = ab.amoeba_plan_src_rank_mask(plan)
+    n = oracle.shard_elems(m, w.src_tp)
+    src = [wl.random_bits(n, seed=w.index * 100 + s) if mask >> s & 1 else None
+           for s in range(w.src_tp)]
+    check_weights(m, w.src_tp, w.dst_tp, w.dst_rank, src)
+
+
+# ------------------------------------------------------------------ KV cache
+def kv_case(k, lens, lay_s, lay_d, n_heads=8, d=8, B=4, layers=2, seed=0, slack=3, elem_bytes=2,
+            pool_extra=5):
+    lens = np.asarray(lens, dtype=np.int32)
+    nb = (np.maximum(lens, 0).astype(np.int64) + B - 1) // B
+    src_pool_blocks = int(nb.sum()) + pool_extra
+    rng = np.random.default_rng(seed)
+    ids = rng.permutation(src_pool_blocks)[:int(nb.sum())]
+    W = max(1, int(nb.max(initial=0))) + 2
+    table = np.full((len(lens), W), -1, dtype=np.int32)
+    p = 0
+    for i, n in enumerate(nb):
+        table[i, :n] = ids[p:p + n]
+        p += int(n)
+    cfg = oracle.KV(kv_layers=layers, n_kv_heads=n_heads, head_dim=d, block_tokens=B,
+                    num_seqs=len(lens), max_blocks_per_seq=W, src_pool_blocks=src_pool_blocks,
+                    dst_pool_blocks=int(nb.sum()) + slack, layout_src=lay_s, layout_dst=lay_d,
+                    elem_bytes=elem_bytes)
+    be = oracle.kv_block_elems(cfg, k)
+    pools = [wl.random_bits(layers * src_pool_blocks * be, seed=seed * 17 + s,
+                            elem_bytes=elem_bytes).reshape(layers, src_pool_blocks, be)
+             for s in range(k)]
+    return cfg, pools, table, lens
+
+
+def check_kv(cfg, k, kp, rp, pools, table, lens, tune=None, expect=oracle.OK):
+    sent = 0xA7
+    st, got_pool, got_table, total, intact = gpu_reshard_kv(cfg, k, kp, rp, pools, table, lens,
+                                                            tune=tune, sentinel=sent)
+    be = oracle.kv_block_elems(cfg, kp)
+    want_pool = np.full((cfg.kv_layers, cfg.dst_pool_blocks, be),
+                        sentinel_elem(cfg.elem_bytes, sent), dtype=oracle.elem_dtype(cfg.elem_bytes))
+    ost, want_table, want_total = oracle.reshard_kv(cfg, k, kp, rp, pools, table, lens, want_pool)
+    assert ost == expect
+    code = {oracle.OK: ab.OK, oracle.ERR_OVERFLOW: ab.ERR_OVERFLOW,
+            oracle.ERR_BLOCK_ID: ab.ERR_BLOCK_ID}[ost]
+    assert st == code
+    assert intact, "bytes outside the destination pool were written"
+    np.testing.assert_array_equal(got_table, want_table)
+    assert total == want_total
+    np.testing.assert_array_equal(got_pool, want_pool)
+
+
+LENS = [13, 1, 8, 0, 22, 5, 16]
+
+
+@pytest.mark.parametrize("lay_s,lay_d", list(itertools.product([HM, TM], repeat=2)))
+@pytest.mark.parametrize("k,kp", [(1, 4), (4, 1), (4, 2), (2, 4), (8, 4), (2, 2), (1, 1), (2, 8)])
+def test_kv_small_all_ranks_all_layout_pairs(k, kp, lay_s, lay_d):
+    cfg, pools, table, lens = kv_case(k, LENS, lay_s, lay_d, seed=k * 5 + kp)
+    for rp in range(kp):
+        check_kv(cfg, k, kp, rp, pools, table, lens)
+
+
+@pytest.mark.parametrize("k,kp", [(2, 3), (3, 2), (6, 4), (3, 12)])
+def test_kv_tp_degrees_that_do_not_divide_each_other(k, kp):
+    cfg, pools, table, lens = kv_case(k, [7, 12, 3], HM, TM, n_heads=12, seed=kp)
+    for rp in range(kp):
+        check_kv(cfg, k, kp, rp, pools, table, lens)
+
+
+@pytest.mark.parametrize("elem_bytes,d", [(1, 16), (2, 8), (4, 4), (2, 4), (2, 2), (2, 1), (1, 1),
+                                          (2, 12), (4, 3)])
+def test_kv_every_vector_width(elem_bytes, d):
+    for lay_s, lay_d in [(HM, HM), (TM, HM)]:
+        cfg, pools, table, lens = kv_case(2, [9, 4, 17], lay_s, lay_d, n_heads=4, d=d, B=4,
+                                          elem_bytes=elem_bytes, seed=d)
+        check_kv(cfg, 2, 4, 1, pools, table, lens)
+        check_kv(cfg, 2, 1, 0, pools, table, lens)
+
+
+@pytest.mark.parametrize("unroll,layers_per_item,grid", [(1, 1, 0), (2, 2, 5), (4, 3, 0),
+                                                         (8, 7, 64), (4, 100, 3)])
+def test_kv_blocks_of_several_tiles_and_launch_shapes(unroll, layers_per_item, grid):
+    """Blocks of 40 KiB (2.5 tiles at the default tile) over 7 layers."""
+    tune = {ab.TUNE_KV_UNROLL: unroll, ab.TUNE_KV_LAYERS: layers_per_item, ab.TUNE_KV_GRID: grid}
+    for lay_s, lay_d in [(HM, HM), (TM, TM), (TM, HM), (HM, TM)]:
+        cfg, pools, table, lens = kv_case(2, [40, 100, 7, 33], lay_s, lay_d, n_heads=10, d=64,
+                                          B=16, layers=7, seed=unroll)
+        check_kv(cfg, 2, 1, 0, pools, table, lens, tune=tune)
+        check_kv(cfg, 2, 5, 3, pools, table, lens, tune=tune)
+
+
+def test_kv_more_than_one_scan_chunk():
+    """3000 sequences: the scan carries its running total across chunks of 1024."""
+    rng = np.random.default_rng(3)
+    lens = rng.integers(0, 40, size=3000)
+    cfg, pools, table, lens = kv_case(1, lens, HM, HM, n_heads=2, d=8, B=4, layers=1, seed=1)
+    check_kv(cfg, 1, 2, 1, pools, table, lens)
+
+
+def test_kv_degenerate_inputs():
+    # all sequences empty
+    cfg, pools, table, lens = kv_case(1, [0, 0, 0], HM, HM)
+    check_kv(cfg, 1, 2, 0, pools, table, lens)
+    # a single token
+    cfg, pools, table, lens = kv_case(2, [1], TM, HM)
+    check_kv(cfg, 2, 1, 0, pools, table, lens)
+    # exact fit of the destination pool
+    cfg, pools, table, lens = kv_case(2, [16, 16], HM, HM, slack=0)
+    check_kv(cfg, 2, 4, 2, pools, table, lens)
+    # no sequences at all
+    cfg, pools, table, lens = kv_case(1, [], HM, HM)
+    check_kv(cfg, 1, 2, 0, pools, table, lens)
+
+
+def test_kv_overflow_conditions_leave_pool_untouched():
+    cfg, pools, table, lens = kv_case(1, [13, 8], HM, HM)
+    nb_total = 4 + 2
+    small = dataclasses.replace(cfg, dst_pool_blocks=nb_total - 1)
+    check_kv(small, 1, 2, 0, pools, table, lens, expect=oracle.ERR_OVERFLOW)
+    narrow = dataclasses.replace(cfg, max_blocks_per_seq=3)
+    check_kv(narrow, 1, 2, 0, pools, table[:, :3].copy(), lens, expect=oracle.ERR_OVERFLOW)
+    neg = lens.copy()
+    neg[0] = -5
+    check_kv(cfg, 1, 2, 0, pools, table, neg, expect=oracle.ERR_OVERFLOW)
+
+
+def test_kv_out_of_range_source_block_is_skipped():
+    cfg, pools, table, lens = kv_case(1, [9, 6], HM, HM, layers=2)
+    bad = table.copy()
+    bad[0, 1] = cfg.src_pool_blocks
+    check_kv(cfg, 1, 2, 1, pools, bad, lens, expect=oracle.ERR_BLOCK_ID)
+    bad[1, 0] = -4
+    check_kv(cfg, 1, 1, 0, pools, bad, lens, expect=oracle.ERR_BLOCK_ID)
+
+
+def test_kv_same_plan_twice_and_status_resets():
+    """A plan's workspace is reused: an error from one call must not leak into the next."""
+    cfg, pools, table, lens = kv_case(1, [9, 6], HM, HM, layers=1)
+    bad = lens.copy()
+    bad[1] = -1
+    check_kv(cfg, 1, 2, 0, pools, table, bad, expect=oracle.ERR_OVERFLOW)
+    check_kv(cfg, 1, 2, 0, pools, table, lens)
+
+
+@pytest.mark.parametrize("lay_s,lay_d", list(itertools.product([HM, TM], repeat=2)))
+def test_kv_tiny_config_all_ranks(lay_s, lay_d):
+    w = wl.WORKLOADS["tiny"]
+    lens = wl.seq_lens(w)
+    table, pool = wl.block_placement(w, lens)
+    nb = int(wl.blocks_per_seq(lens, w.block_tokens).sum())
+    cfg = oracle.KV(kv_layers=w.n_layers, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                    block_tokens=w.block_tokens, num_seqs=w.num_seqs,
+                    max_blocks_per_seq=table.shape[1], src_pool_blocks=pool,
+                    dst_pool_blocks=nb + 64, layout_src=lay_s, layout_dst=lay_d)
+    be = oracle.kv_block_elems(cfg, w.src_tp)
+    pools = [wl.payload16(w.n_layers * pool * be, seed=77 + s, dtype=w.dtype)
+             .reshape(w.n_layers, pool, be) for s in range(w.src_tp)]
+    for rp in range(w.dst_tp):
+        check_kv(cfg, w.src_tp, w.dst_tp, rp, pools, table, lens)
+
+
+@pytest.mark.parametrize("name", ["llama7b", "llama13b", "gqa70b", "long8b"])
+@pytest.mark.parametrize("lay_s,lay_d", [(HM, HM), (TM, HM)])
+def test_kv_real_block_shapes(name, lay_s, lay_d):
+    """Real block geometry and table of each benchmark workload, two layers, the first
+    sequences only so the oracle finishes in seconds."""
+    w = wl.WORKLOADS[name]
+    lens = wl.seq_lens(w)
+    keep = 6 if name != "long8b" else 10      # long8b: one 32K sequence plus short ones
+    sel = np.r_[0:1, 8:8 + keep - 1] if name == "long8b" else np.r_[0:keep]
+    lens = lens[sel]
+    w2 = w.scaled(num_seqs=len(lens))
+    table, pool = wl.block_placement(w2, lens)
+    nb = int(wl.blocks_per_seq(lens, w.block_tokens).sum())
+    cfg = oracle.KV(kv_layers=2, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                    block_tokens=w.block_tokens, num_seqs=len(lens),
+                    max_blocks_per_seq=table.shape[1], src_pool_blocks=pool,
+                    dst_pool_blocks=nb + 64, layout_src=lay_s, layout_dst=lay_d)
+    plan_mask = 0
+    hd, hs = w.n_kv_heads // w.dst_tp, w.n_kv_heads // w.src_tp
+    for h in range(w.dst_rank * hd, (w.dst_rank + 1) * hd):
+        plan_mask |= 1 << (h // hs)
+    be = oracle.kv_block_elems(cfg, w.src_tp)
+    pools = [wl.random_bits(2 * pool * be, seed=w.index * 10 + s).reshape(2, pool, be)
+             if plan_mask >> s & 1 else None for s in range(w.src_tp)]
+    check_kv(cfg, w.src_tp, w.dst_tp, w.dst_rank, pools, table, lens)
