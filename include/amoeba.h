@@ -71,13 +71,14 @@ enum {
 
 /* Knobs for amoeba_plan_tune(); 0 restores the built-in choice. */
 enum {
-  AMOEBA_TUNE_W_GRID = 0,    /* workgroups of the weight kernel (0: one per tile)       */
-  AMOEBA_TUNE_W_UNROLL = 1,  /* 16-byte vectors per lane per tile: 1, 2, 4 or 8          */
-  AMOEBA_TUNE_KV_GRID = 2,   /* workgroups of the KV regroup kernel                      */
-  AMOEBA_TUNE_KV_UNROLL = 3, /* vectors per lane per tile: 1, 2, 4 or 8                  */
-  AMOEBA_TUNE_KV_LAYERS = 4, /* layers one work item walks through                       */
-  AMOEBA_TUNE_NONTEMPORAL = 5, /* 1: streaming (nt) loads/stores, 2: plain               */
-  AMOEBA_TUNE_KV_STAGED = 6  /* 1: LDS-staged path for layout-converting regroup, 2: direct */
+  AMOEBA_TUNE_W_GRID = 0,      /* workgroups of the weight kernel (0: one per tile)          */
+  AMOEBA_TUNE_W_UNROLL = 1,    /* 16-byte vectors per lane per tile: 1, 2, 4 or 8            */
+  AMOEBA_TUNE_W_THREADS = 2,   /* lanes per workgroup: 64, 128 or 256                        */
+  AMOEBA_TUNE_KV_GRID = 3,     /* workgroups per layer of the KV regroup kernel              */
+  AMOEBA_TUNE_KV_UNROLL = 4,   /* vectors per lane per tile: 1, 2 or 4                       */
+  AMOEBA_TUNE_KV_THREADS = 5,  /* lanes per workgroup: 64 or 256                             */
+  AMOEBA_TUNE_NONTEMPORAL = 6, /* 1: streaming (nt) loads/stores, 2: plain                   */
+  AMOEBA_TUNE_KV_STAGED = 7    /* 1: LDS-staged layout-converting regroup, 2: direct         */
 };
 
 /* Caller-owned POD; amoeba_plan() copies it. */
@@ -181,6 +182,15 @@ int amoeba_plan_segment(const amoeba_plan_t* plan, int index, int64_t out[7]);
 /* Launch-shape knobs (AMOEBA_TUNE_*), for measurement sweeps.  Not thread-safe
  * against concurrent reshard calls on the same plan. */
 int amoeba_plan_tune(amoeba_plan_t* plan, int knob, int value);
+
+/* Measurement aid, not part of the reshard: a plain device-to-device streaming copy
+ * with the same access shape as the reshard kernels (16 B per lane, `unroll` loads in
+ * flight per lane: 1, 2, 4 or 8; `grid` workgroups, 0 = one per tile; nontemporal as in
+ * AMOEBA_TUNE_NONTEMPORAL).  Gives the copy rate this GPU reaches and a transfer of
+ * known size to calibrate HBM traffic counters.  dst, src: DEVICE pointers, 16-byte
+ * aligned, non-overlapping; bytes a multiple of 16. */
+int amoeba_copy_baseline(void* dst, const void* src, size_t bytes, int unroll, int grid,
+                         int nontemporal, void* stream);
 
 /* Text of the calling thread's last error ("" if none). */
 const char* amoeba_last_error(void);

@@ -20,8 +20,8 @@ OK, ERR_INVALID_ARG, ERR_HIP, ERR_OVERFLOW, ERR_BLOCK_ID = 0, 1, 2, 3, 4
 
 T_Q, T_K, T_V, T_O, T_GATE, T_UP, T_DOWN = range(7)
 
-TUNE_W_GRID, TUNE_W_UNROLL, TUNE_KV_GRID, TUNE_KV_UNROLL, TUNE_KV_LAYERS, TUNE_NONTEMPORAL, \
-    TUNE_KV_STAGED = range(7)
+TUNE_W_GRID, TUNE_W_UNROLL, TUNE_W_THREADS, TUNE_KV_GRID, TUNE_KV_UNROLL, TUNE_KV_THREADS, \
+    TUNE_NONTEMPORAL, TUNE_KV_STAGED = range(8)
 
 MAX_TP = 16
 
@@ -31,7 +31,7 @@ EXPORTS = [
     "amoeba_kv_status", "amoeba_plan_shard_bytes", "amoeba_plan_kv_block_bytes",
     "amoeba_plan_src_rank_mask", "amoeba_plan_kv_rank_mask", "amoeba_plan_tensor_info",
     "amoeba_plan_kv_stride_order", "amoeba_plan_num_segments", "amoeba_plan_segment",
-    "amoeba_plan_tune", "amoeba_last_error",
+    "amoeba_plan_tune", "amoeba_copy_baseline", "amoeba_last_error",
 ]
 
 
@@ -109,6 +109,8 @@ def lib() -> ctypes.CDLL:
     L.amoeba_plan_segment.argtypes = [vp, i32, ctypes.POINTER(i64)]
     L.amoeba_plan_tune.restype = i32
     L.amoeba_plan_tune.argtypes = [vp, i32, i32]
+    L.amoeba_copy_baseline.restype = i32
+    L.amoeba_copy_baseline.argtypes = [vp, vp, ctypes.c_size_t, i32, i32, i32, vp]
     L.amoeba_last_error.restype = ctypes.c_char_p
     L.amoeba_last_error.argtypes = []
     _lib = L
@@ -256,5 +258,13 @@ def amoeba_plan_segment(plan: Plan, index: int):
 
 def amoeba_plan_tune(plan: Plan, knob: int, value: int) -> None:
     rc = lib().amoeba_plan_tune(plan.handle, knob, value)
+    if rc != OK:
+        raise AmoebaError(rc, amoeba_last_error())
+
+
+def amoeba_copy_baseline(dst, src, nbytes: int, unroll: int = 4, grid: int = 0,
+                         nontemporal: int = 1, stream=None) -> None:
+    rc = lib().amoeba_copy_baseline(_ptr(dst), _ptr(src), nbytes, unroll, grid, nontemporal,
+                                    _stream_handle(stream))
     if rc != OK:
         raise AmoebaError(rc, amoeba_last_error())

@@ -9,7 +9,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libamoeba.so")
-SOURCES = ["api.cpp", "plan.cpp", "reshard_weights.hip", "reshard_kv.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "reshard_weights.hip", "reshard_kv.hip",
+           "copy_baseline.hip"]
 
 
 def hipcc() -> str:

@@ -194,6 +194,16 @@ int amoeba_plan_segment(const amoeba_plan_t* plan, int index, int64_t out[7]) {
   return AMOEBA_OK;
 }
 
+int amoeba_copy_baseline(void* dst, const void* src, size_t bytes, int unroll, int grid,
+                         int nontemporal, void* stream) {
+  if (!dst || !src) { set_error("amoeba_copy_baseline: NULL pointer"); return AMOEBA_ERR_INVALID_ARG; }
+  std::string err;
+  const int rc = amoeba::launch_copy_baseline(dst, src, bytes, unroll, grid, nontemporal != 2,
+                                              static_cast<hipStream_t>(stream), &err);
+  if (rc != AMOEBA_OK) set_error("amoeba_copy_baseline: " + err);
+  return rc;
+}
+
 int amoeba_plan_tune(amoeba_plan_t* plan, int knob, int value) {
   if (!plan || value < 0) { set_error("amoeba_plan_tune: bad plan or value"); return AMOEBA_ERR_INVALID_ARG; }
   switch (knob) {
@@ -201,7 +211,8 @@ int amoeba_plan_tune(amoeba_plan_t* plan, int knob, int value) {
     case AMOEBA_TUNE_W_UNROLL: plan->tune.w_unroll = value; break;
     case AMOEBA_TUNE_KV_GRID: plan->tune.kv_grid = value; break;
     case AMOEBA_TUNE_KV_UNROLL: plan->tune.kv_unroll = value; break;
-    case AMOEBA_TUNE_KV_LAYERS: plan->tune.kv_layers = value; break;
+    case AMOEBA_TUNE_W_THREADS: plan->tune.w_threads = value; break;
+    case AMOEBA_TUNE_KV_THREADS: plan->tune.kv_threads = value; break;
     case AMOEBA_TUNE_NONTEMPORAL: plan->tune.nontemporal = value; break;
     case AMOEBA_TUNE_KV_STAGED: plan->tune.kv_staged = value; break;
     default: set_error("amoeba_plan_tune: unknown knob"); return AMOEBA_ERR_INVALID_ARG;

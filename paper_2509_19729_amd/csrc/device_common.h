@@ -18,18 +18,25 @@ template <> struct VecOf<4> { using type = uint32_t; };
 template <> struct VecOf<2> { using type = uint16_t; };
 template <> struct VecOf<1> { using type = uint8_t; };
 
+// Every buffer the library touches is device global memory; saying so in the pointer
+// type keeps the accesses on the global_load/global_store path even when the address
+// went through a select or a table.
+#define AMOEBA_GLOBAL __attribute__((address_space(1)))
+
 template <bool NT, typename V>
 __device__ __forceinline__ V ld(const char* p) {
-  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
-  return *reinterpret_cast<const V*>(p);
+  const AMOEBA_GLOBAL V* g = (const AMOEBA_GLOBAL V*)(uintptr_t)p;
+  if (NT) return __builtin_nontemporal_load(g);
+  return *g;
 }
 
 template <bool NT, typename V>
 __device__ __forceinline__ void st(char* p, V v) {
+  AMOEBA_GLOBAL V* g = (AMOEBA_GLOBAL V*)(uintptr_t)p;
   if (NT)
-    __builtin_nontemporal_store(v, reinterpret_cast<V*>(p));
+    __builtin_nontemporal_store(v, g);
   else
-    *reinterpret_cast<V*>(p) = v;
+    *g = v;
 }
 
 constexpr int kThreads = 256;  // 4 wavefronts of 64 lanes per workgroup

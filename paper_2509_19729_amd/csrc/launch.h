@@ -4,6 +4,8 @@
 
 #include <string>
 
+#include "../../include/amoeba.h"
+
 struct amoeba_plan_s;
 
 namespace amoeba {
@@ -18,5 +20,8 @@ int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards
 int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
                       const int32_t* src_block_tables, const int32_t* seq_lens, void* dst_blocks,
                       int32_t* dst_block_tables, hipStream_t stream, std::string* err);
+
+int launch_copy_baseline(void* dst, const void* src, size_t bytes, int unroll, int grid, bool nt,
+                         hipStream_t stream, std::string* err);
 
 }  // namespace amoeba

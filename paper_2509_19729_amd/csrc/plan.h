@@ -31,8 +31,8 @@ struct Segment {
 };
 
 struct Tuning {
-  int w_grid = 0, w_unroll = 0, kv_grid = 0, kv_unroll = 0, kv_layers = 0, nontemporal = 0,
-      kv_staged = 0;
+  int w_grid = 0, w_unroll = 0, w_threads = 0, kv_grid = 0, kv_unroll = 0, kv_threads = 0,
+      nontemporal = 0, kv_staged = 0;
 };
 
 }  // namespace amoeba

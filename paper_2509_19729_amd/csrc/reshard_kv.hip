@@ -15,9 +15,11 @@
 //                    1024 sequences; validates lengths / row width / pool size.
 //   kv_table_kernel  one lane per table cell: writes the new table and a flat list
 //                    "new block id -> source block id" (ids range-checked here).
-//   kv_regroup_kernel persistent workgroups stride over work items
-//                    (layer group, new block, tile); a tile is a run of 16-byte
-//                    vectors contiguous in the destination block.  A lane turns its
+//   kv_regroup_kernel one workgroup per (layer, new block, tile), layer on grid.y;
+//                    a tile is a run of 16-byte vectors contiguous in the
+//                    destination block.  The number of blocks in use is only
+//                    known on the device, so the grid covers the pool's capacity
+//                    (capped) and idle workgroups leave at once.  A lane turns its
 //                    vector index into (head, K/V*token, d-offset) for the
 //                    destination layout with multiply-high divisions, maps the head
 //                    to (source rank, local head) and rebuilds the index for the
@@ -122,49 +124,49 @@ kv_table_kernel(const int32_t* __restrict__ seq_lens, const int32_t* __restrict_
 
 struct KVArgs {
   const char* src[AMOEBA_MAX_TP];
+  const char* src_lo;        // == src[rank_lo]
+  const char* src_hi;        // == src[rank_hi]
   char* dst;
   const int32_t* ws;
   uint64_t src_layer_stride, dst_layer_stride;  // bytes between layers of a pool
   uint64_t src_block_bytes, dst_block_bytes;
   uint32_t num_seqs;
-  uint32_t layers, layers_per_item, layer_groups;
   uint32_t block_vecs;       // vectors in one destination block
   FastDiv tiles_per_block;
   uint32_t head0;            // first global head the target rank owns
+  uint32_t rank_lo, rank_hi; // first and last source rank that own one of those heads
+  uint32_t n_src;            // rank_hi - rank_lo + 1
   FastDiv heads_src;         // heads per source rank
   FastDiv heads_dst;         // heads per target rank
   FastDiv head_vecs;         // vectors of one head in a header-centric block: 2 * B * dv
   FastDiv dv;                // vectors of one head vector (d * elem_bytes / VEC)
 };
 
-template <int SL, int DL, int VEC, int UNROLL, bool NT>
-__global__ void __launch_bounds__(kThreads) kv_regroup_kernel(const KVArgs a) {
+// blockIdx.y = layer; blockIdx.x strides over (new block, tile) of that layer.
+// `ws` is only read here (the scan and table kernels that fill it have finished),
+// which lets the uniform lookups go through scalar loads.
+template <int SL, int DL, int VEC, int THREADS, int UNROLL, bool NT>
+__global__ void __launch_bounds__(THREADS)
+kv_regroup_kernel(const KVArgs a, const int32_t* __restrict__ ws) {
   using V = typename VecOf<VEC>::type;
-  constexpr uint32_t kTileVecs = kThreads * UNROLL;
-  __shared__ const char* src_s[AMOEBA_MAX_TP];
+  constexpr uint32_t kTileVecs = THREADS * UNROLL;
   const uint32_t tid = threadIdx.x;
-  if (tid < AMOEBA_MAX_TP) src_s[tid] = a.src[tid];
-  __syncthreads();
-
-  const uint32_t total = (uint32_t)a.ws[kWsTotal];
-  const int32_t* worklist = a.ws + kWsHeader + a.num_seqs;
-  const uint32_t per_group = total * a.tiles_per_block.d;
-  const uint32_t n_items = per_group * a.layer_groups;  // < 2^32, bounded on the host
+  const uint32_t layer = blockIdx.y;
+  const uint32_t total = (uint32_t)ws[kWsTotal];
+  const int32_t* __restrict__ worklist = ws + kWsHeader + a.num_seqs;
+  const uint32_t n_items = total * a.tiles_per_block.d;  // < 2^32, bounded on the host
 
   for (uint32_t w = blockIdx.x; w < n_items; w += gridDim.x) {
-    const uint32_t lg = w / per_group;
-    const uint32_t r = w - lg * per_group;
-    const uint32_t b = fd_div(r, a.tiles_per_block);
-    const uint32_t tile = r - b * a.tiles_per_block.d;
-    const int32_t sb = worklist[b];
-    if (sb < 0) continue;  // source id was out of range: leave the block alone
+    const uint32_t b = fd_div(w, a.tiles_per_block);
+    const uint32_t tile = w - b * a.tiles_per_block.d;
+    const int32_t sb = worklist[b];  // -1: the source id was out of range, block is skipped
 
     const char* sp[UNROLL];
     uint32_t dvec[UNROLL];
     bool live[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-      const uint32_t v = tile * kTileVecs + u * kThreads + tid;
+      const uint32_t v = tile * kTileVecs + u * THREADS + tid;
       live[u] = v < a.block_vecs;
       dvec[u] = v;
       uint32_t hp, within, ct = 0, x = 0;  // within: index inside one header-centric head
@@ -188,54 +190,65 @@ __global__ void __launch_bounds__(kThreads) kv_regroup_kernel(const KVArgs a) {
       const uint32_t svec = (SL == AMOEBA_KV_HEAD_MAJOR)
                                 ? hs * a.head_vecs.d + within
                                 : (ct * a.heads_src.d + hs) * a.dv.d + x;
-      sp[u] = src_s[live[u] ? s : 0] + uint64_t(sb) * a.src_block_bytes + uint64_t(svec) * VEC;
+      // Source pool of the owning rank.  Nearly always one or two ranks feed a target
+      // rank; then the choice is a select between two scalar-loaded pointers and
+      // costs no memory access.
+      const char* pool;
+      if (a.n_src <= 2)
+        pool = (s == a.rank_lo) ? a.src_lo : a.src_hi;
+      else
+        pool = a.src[live[u] ? s : a.rank_lo];  // s < src_tp on live lanes
+      sp[u] = pool + uint64_t(svec) * VEC;
     }
-    char* dp = a.dst + uint64_t(b) * a.dst_block_bytes;
-
-    const uint32_t l0 = lg * a.layers_per_item;
-    const uint32_t l1 = min(a.layers, l0 + a.layers_per_item);
-    for (uint32_t l = l0; l < l1; ++l) {
-      const uint64_t so = uint64_t(l) * a.src_layer_stride, dof = uint64_t(l) * a.dst_layer_stride;
-      V val[UNROLL];
+    const uint64_t soff = uint64_t(layer) * a.src_layer_stride + uint64_t(sb) * a.src_block_bytes;
+    char* dp = a.dst + uint64_t(layer) * a.dst_layer_stride + uint64_t(b) * a.dst_block_bytes;
+    V val[UNROLL];
 #pragma unroll
-      for (int u = 0; u < UNROLL; ++u)
-        if (live[u]) val[u] = ld<NT, V>(sp[u] + so);
-#pragma unroll
-      for (int u = 0; u < UNROLL; ++u)
-        if (live[u]) st<NT, V>(dp + dof + uint64_t(dvec[u]) * VEC, val[u]);
+    for (int u = 0; u < UNROLL; ++u) {
+      live[u] = live[u] && sb >= 0;
+      if (live[u]) val[u] = ld<NT, V>(sp[u] + soff);
     }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+      if (live[u]) st<NT, V>(dp + uint64_t(dvec[u]) * VEC, val[u]);
   }
 }
 
 namespace {
 
-template <int SL, int DL, int VEC, int UNROLL>
+template <int SL, int DL, int VEC, int THREADS, int UNROLL>
 void launch_nt(bool nt, dim3 grid, hipStream_t stream, const KVArgs& a) {
   if (nt)
-    hipLaunchKernelGGL((kv_regroup_kernel<SL, DL, VEC, UNROLL, true>), grid, dim3(kThreads), 0,
-                       stream, a);
+    hipLaunchKernelGGL((kv_regroup_kernel<SL, DL, VEC, THREADS, UNROLL, true>), grid,
+                       dim3(THREADS), 0, stream, a, a.ws);
   else
-    hipLaunchKernelGGL((kv_regroup_kernel<SL, DL, VEC, UNROLL, false>), grid, dim3(kThreads), 0,
-                       stream, a);
+    hipLaunchKernelGGL((kv_regroup_kernel<SL, DL, VEC, THREADS, UNROLL, false>), grid,
+                       dim3(THREADS), 0, stream, a, a.ws);
+}
+
+template <int SL, int DL, int THREADS>
+void launch_unroll(int unroll, bool nt, dim3 grid, hipStream_t stream, const KVArgs& a) {
+  switch (unroll) {
+    case 2: launch_nt<SL, DL, 16, THREADS, 2>(nt, grid, stream, a); break;
+    case 4: launch_nt<SL, DL, 16, THREADS, 4>(nt, grid, stream, a); break;
+    default: launch_nt<SL, DL, 16, THREADS, 1>(nt, grid, stream, a); break;
+  }
 }
 
 template <int SL, int DL>
-void launch_vec(int vec, int unroll, bool nt, dim3 grid, hipStream_t stream, const KVArgs& a) {
+void launch_vec(int vec, int threads, int unroll, bool nt, dim3 grid, hipStream_t stream,
+                const KVArgs& a) {
   if (vec == 16) {
-    switch (unroll) {
-      case 1: launch_nt<SL, DL, 16, 1>(nt, grid, stream, a); break;
-      case 2: launch_nt<SL, DL, 16, 2>(nt, grid, stream, a); break;
-      case 8: launch_nt<SL, DL, 16, 8>(nt, grid, stream, a); break;
-      default: launch_nt<SL, DL, 16, 4>(nt, grid, stream, a); break;
-    }
+    if (threads == 64) launch_unroll<SL, DL, 64>(unroll, nt, grid, stream, a);
+    else launch_unroll<SL, DL, 256>(unroll, nt, grid, stream, a);
   } else if (vec == 8) {
-    launch_nt<SL, DL, 8, 4>(nt, grid, stream, a);
+    launch_nt<SL, DL, 8, 256, 1>(true, grid, stream, a);
   } else if (vec == 4) {
-    launch_nt<SL, DL, 4, 4>(nt, grid, stream, a);
+    launch_nt<SL, DL, 4, 256, 1>(true, grid, stream, a);
   } else if (vec == 2) {
-    launch_nt<SL, DL, 2, 4>(nt, grid, stream, a);
+    launch_nt<SL, DL, 2, 256, 1>(true, grid, stream, a);
   } else {
-    launch_nt<SL, DL, 1, 4>(nt, grid, stream, a);
+    launch_nt<SL, DL, 1, 256, 1>(true, grid, stream, a);
   }
 }
 
@@ -287,8 +300,9 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
     a.src[r] = static_cast<const char*>(src_blocks[r]);
   }
   const int vec = common_alignment(bits);
-  int unroll = p->tune.kv_unroll;
-  if (vec != 16 || (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8)) unroll = 4;
+  int unroll = p->tune.kv_unroll, threads = p->tune.kv_threads;
+  if (vec != 16 || (unroll != 2 && unroll != 4)) unroll = 1;
+  if (vec != 16 || threads != 64) threads = 256;
   const bool nt = p->tune.nontemporal != 2;
 
   // 1. scan
@@ -307,13 +321,11 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
   }
   // 3. regroup
   const uint64_t block_vecs = uint64_t(p->block_bytes_dst) / vec;
-  const uint64_t tile_vecs = uint64_t(kThreads) * unroll;
+  const uint64_t tile_vecs = uint64_t(threads) * unroll;
   const uint64_t tiles_per_block = (block_vecs + tile_vecs - 1) / tile_vecs;
-  uint32_t lpi = p->tune.kv_layers > 0 ? uint32_t(p->tune.kv_layers) : 1;
-  lpi = std::min<uint32_t>(lpi, uint32_t(s.kv_layers));
-  const uint32_t groups = (uint32_t(s.kv_layers) + lpi - 1) / lpi;
-  const uint64_t max_items = uint64_t(s.dst_pool_blocks) * tiles_per_block * groups;
-  if (block_vecs >= (uint64_t(1) << 32) - 65536 || max_items >= (uint64_t(1) << 32)) {
+  const uint64_t max_items = uint64_t(s.dst_pool_blocks) * tiles_per_block;  // per layer
+  if (block_vecs >= (uint64_t(1) << 32) - 65536 || max_items >= (uint64_t(1) << 32) - (1 << 24) ||
+      s.kv_layers > 65535) {
     *err = "KV pool too large for 32-bit work indexing";
     return AMOEBA_ERR_INVALID_ARG;
   }
@@ -325,31 +337,35 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
   a.src_block_bytes = uint64_t(p->block_bytes_src);
   a.dst_block_bytes = uint64_t(p->block_bytes_dst);
   a.num_seqs = uint32_t(s.num_seqs);
-  a.layers = uint32_t(s.kv_layers);
-  a.layers_per_item = lpi;
-  a.layer_groups = groups;
   a.block_vecs = uint32_t(block_vecs);
   a.tiles_per_block = make_fastdiv(uint32_t(tiles_per_block));
   a.head0 = uint32_t(p->rp * p->heads_dst);
+  a.rank_lo = a.head0 / uint32_t(p->heads_src);
+  a.rank_hi = (a.head0 + uint32_t(p->heads_dst) - 1) / uint32_t(p->heads_src);
+  a.n_src = a.rank_hi - a.rank_lo + 1;
+  a.src_lo = a.src[a.rank_lo];
+  a.src_hi = a.src[a.rank_hi];
   a.heads_src = make_fastdiv(uint32_t(p->heads_src));
   a.heads_dst = make_fastdiv(uint32_t(p->heads_dst));
   const uint32_t dv = uint32_t(head_vec_bytes / vec);
   a.dv = make_fastdiv(dv);
   a.head_vecs = make_fastdiv(uint32_t(2u * uint32_t(s.kv_block_tokens) * dv));
 
-  uint64_t grid = uint64_t(p->n_cu > 0 ? p->n_cu : 256) * 8;
+  // One workgroup per tile of the pool's capacity, capped so that a mostly empty pool
+  // does not pay for millions of idle workgroups; past the cap workgroups stride.
+  uint64_t grid = std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 23) / uint64_t(s.kv_layers));
   if (p->tune.kv_grid > 0) grid = uint64_t(p->tune.kv_grid);
   grid = std::min<uint64_t>(grid, max_items);
-  const dim3 g{uint32_t(grid)};
+  const dim3 g(uint32_t(grid), uint32_t(s.kv_layers));
   const bool sh = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR, dh = s.kv_layout_dst == AMOEBA_KV_HEAD_MAJOR;
   if (sh && dh)
-    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, unroll, nt, g, stream, a);
+    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, threads, unroll, nt, g, stream, a);
   else if (sh && !dh)
-    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, unroll, nt, g, stream, a);
+    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, threads, unroll, nt, g, stream, a);
   else if (!sh && dh)
-    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, unroll, nt, g, stream, a);
+    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, threads, unroll, nt, g, stream, a);
   else
-    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, unroll, nt, g, stream, a);
+    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, threads, unroll, nt, g, stream, a);
   if (!hip_ok("kv regroup kernel launch failed", err)) return AMOEBA_ERR_HIP;
   return AMOEBA_OK;
 }

@@ -8,9 +8,12 @@
 //
 // Mapping to the machine.  The work is HBM-bound (every byte is read once and
 // written once), so: each lane moves 16 bytes per access, a workgroup of 256
-// lanes owns a tile of UNROLL x 4 KiB that is contiguous in the destination,
+// lanes owns a tile of UNROLL x THREADS x 16 B that is contiguous in the destination,
 // all loads of a tile are issued before its first store, and accesses carry the
-// non-temporal hint because nothing is reused.  Tiles are numbered in
+// non-temporal hint because nothing is reused.  Measured on MI355X the best shape
+// is the smallest one: one 16-byte vector per lane and one workgroup per tile,
+// leaving the overlap of reads and writes to the many short-lived wavefronts in
+// flight (larger tiles or persistent grid-stride loops cost 5-15 %).  Tiles are numbered in
 // destination order (layer, segment, position) so that the workgroups in flight
 // at any time sweep one contiguous window of the destination.  Within a strided
 // rectangle the lane's vector index n is split into (row, column) with a
@@ -45,10 +48,10 @@ struct WArgs {
   FastDiv tiles_per_layer;
 };
 
-template <int VEC, int UNROLL, bool NT>
-__global__ void __launch_bounds__(kThreads) reshard_weights_kernel(const WArgs a) {
+template <int VEC, int THREADS, int UNROLL, bool NT>
+__global__ void __launch_bounds__(THREADS) reshard_weights_kernel(const WArgs a) {
   using V = typename VecOf<VEC>::type;
-  constexpr uint32_t kTileVecs = kThreads * UNROLL;
+  constexpr uint32_t kTileVecs = THREADS * UNROLL;
   const uint32_t tid = threadIdx.x;
 
   for (uint32_t w = blockIdx.x; w < a.total_tiles; w += gridDim.x) {
@@ -70,7 +73,7 @@ __global__ void __launch_bounds__(kThreads) reshard_weights_kernel(const WArgs a
     bool live[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-      const uint32_t n = n0 + u * kThreads;
+      const uint32_t n = n0 + u * THREADS;
       live[u] = n < s.total_vecs;
       const uint32_t row = fd_div(n, s.row_vecs);
       const uint32_t col = n - row * s.row_vecs.d;
@@ -86,32 +89,40 @@ __global__ void __launch_bounds__(kThreads) reshard_weights_kernel(const WArgs a
 
 namespace {
 
-template <int VEC, int UNROLL>
+template <int VEC, int THREADS, int UNROLL>
 void launch_one(bool nt, dim3 grid, hipStream_t stream, const WArgs& a) {
   if (nt)
-    hipLaunchKernelGGL((reshard_weights_kernel<VEC, UNROLL, true>), grid, dim3(kThreads), 0,
-                       stream, a);
+    hipLaunchKernelGGL((reshard_weights_kernel<VEC, THREADS, UNROLL, true>), grid, dim3(THREADS),
+                       0, stream, a);
   else
-    hipLaunchKernelGGL((reshard_weights_kernel<VEC, UNROLL, false>), grid, dim3(kThreads), 0,
-                       stream, a);
+    hipLaunchKernelGGL((reshard_weights_kernel<VEC, THREADS, UNROLL, false>), grid, dim3(THREADS),
+                       0, stream, a);
 }
 
-void dispatch(int vec, int unroll, bool nt, dim3 grid, hipStream_t stream, const WArgs& a) {
+template <int THREADS>
+void dispatch_unroll(int unroll, bool nt, dim3 grid, hipStream_t stream, const WArgs& a) {
+  switch (unroll) {
+    case 2: launch_one<16, THREADS, 2>(nt, grid, stream, a); break;
+    case 4: launch_one<16, THREADS, 4>(nt, grid, stream, a); break;
+    case 8: launch_one<16, THREADS, 8>(nt, grid, stream, a); break;
+    default: launch_one<16, THREADS, 1>(nt, grid, stream, a); break;
+  }
+}
+
+void dispatch(int vec, int threads, int unroll, bool nt, dim3 grid, hipStream_t stream,
+              const WArgs& a) {
   if (vec == 16) {
-    switch (unroll) {
-      case 1: launch_one<16, 1>(nt, grid, stream, a); break;
-      case 2: launch_one<16, 2>(nt, grid, stream, a); break;
-      case 8: launch_one<16, 8>(nt, grid, stream, a); break;
-      default: launch_one<16, 4>(nt, grid, stream, a); break;
-    }
+    if (threads == 64) dispatch_unroll<64>(unroll, nt, grid, stream, a);
+    else if (threads == 128) dispatch_unroll<128>(unroll, nt, grid, stream, a);
+    else dispatch_unroll<256>(unroll, nt, grid, stream, a);
   } else if (vec == 8) {
-    launch_one<8, 4>(nt, grid, stream, a);
+    launch_one<8, 256, 1>(nt, grid, stream, a);
   } else if (vec == 4) {
-    launch_one<4, 4>(nt, grid, stream, a);
+    launch_one<4, 256, 1>(nt, grid, stream, a);
   } else if (vec == 2) {
-    launch_one<2, 4>(nt, grid, stream, a);
+    launch_one<2, 256, 1>(nt, grid, stream, a);
   } else {
-    launch_one<1, 4>(nt, grid, stream, a);
+    launch_one<1, 256, 1>(nt, grid, stream, a);
   }
 }
 
@@ -142,10 +153,12 @@ int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards
     bits |= s0;
   }
   const int vec = common_alignment(bits);
-  int unroll = p->tune.w_unroll;
-  if (vec != 16 || (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8)) unroll = 4;
+  int unroll = p->tune.w_unroll, threads = p->tune.w_threads;
+  if (vec != 16 || (unroll != 2 && unroll != 4 && unroll != 8)) unroll = 1;
+  if (vec != 16) threads = 256;
+  else if (threads != 128 && threads != 256) threads = 64;  // one wavefront per 1 KiB tile
   const bool nt = p->tune.nontemporal != 2;
-  const uint64_t tile_vecs = uint64_t(kThreads) * unroll;
+  const uint64_t tile_vecs = uint64_t(threads) * unroll;
 
   const size_t n = p->segments.size();
   for (size_t first = 0; first < n; first += kMaxSegs) {
@@ -185,7 +198,7 @@ int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards
     a.tiles_per_layer = make_fastdiv(uint32_t(tiles));
     uint64_t grid = total_tiles;
     if (p->tune.w_grid > 0) grid = std::min<uint64_t>(grid, uint64_t(p->tune.w_grid));
-    dispatch(vec, unroll, nt, dim3(uint32_t(grid)), stream, a);
+    dispatch(vec, threads, unroll, nt, dim3(uint32_t(grid)), stream, a);
     const hipError_t rc = hipGetLastError();
     if (rc != hipSuccess) {
       *err = std::string("weight kernel launch failed: ") + hipGetErrorString(rc);

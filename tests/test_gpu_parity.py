@@ -65,13 +65,13 @@ def test_weights_every_vector_width(elem_bytes, hidden, d, ffn):
             check_weights(m, k, kp, rp, src)
 
 
-@pytest.mark.parametrize("unroll", [1, 2, 4, 8])
+@pytest.mark.parametrize("unroll,threads", [(1, 256), (2, 64), (4, 128), (8, 256), (1, 64)])
 @pytest.mark.parametrize("grid", [0, 7, 300])
-def test_weights_several_tiles_and_ragged_tails(unroll, grid):
+def test_weights_several_tiles_and_ragged_tails(unroll, threads, grid):
     """Segments of 2.6 tiles and more, rows that are not a multiple of the tile, both
     the one-workgroup-per-tile launch and the grid-stride launch."""
     m = oracle.Model(n_layers=3, hidden=520, n_q_heads=8, n_kv_heads=4, head_dim=40, ffn_dim=1208)
-    tune = {ab.TUNE_W_UNROLL: unroll, ab.TUNE_W_GRID: grid}
+    tune = {ab.TUNE_W_UNROLL: unroll, ab.TUNE_W_GRID: grid, ab.TUNE_W_THREADS: threads}
     for k, kp, rp in [(4, 2, 1), (1, 4, 3), (2, 1, 0)]:
         check_weights(m, k, kp, rp, rand_shards(m, k, seed=unroll), tune=tune)
 
@@ -210,11 +210,12 @@ def test_kv_every_vector_width(elem_bytes, d):
         check_kv(cfg, 2, 1, 0, pools, table, lens)
 
 
-@pytest.mark.parametrize("unroll,layers_per_item,grid", [(1, 1, 0), (2, 2, 5), (4, 3, 0),
-                                                         (8, 7, 64), (4, 100, 3)])
-def test_kv_blocks_of_several_tiles_and_launch_shapes(unroll, layers_per_item, grid):
-    """Blocks of 40 KiB (2.5 tiles at the default tile) over 7 layers."""
-    tune = {ab.TUNE_KV_UNROLL: unroll, ab.TUNE_KV_LAYERS: layers_per_item, ab.TUNE_KV_GRID: grid}
+@pytest.mark.parametrize("unroll,threads,grid", [(1, 256, 0), (2, 64, 5), (4, 256, 0),
+                                                 (4, 64, 64), (1, 64, 3), (2, 256, 1)])
+def test_kv_blocks_of_several_tiles_and_launch_shapes(unroll, threads, grid):
+    """Blocks of 40 KiB (10 tiles at the default tile, 2.5 at the largest) over 7 layers,
+    one workgroup per tile and grid-stride launches."""
+    tune = {ab.TUNE_KV_UNROLL: unroll, ab.TUNE_KV_THREADS: threads, ab.TUNE_KV_GRID: grid}
     for lay_s, lay_d in [(HM, HM), (TM, TM), (TM, HM), (HM, TM)]:
         cfg, pools, table, lens = kv_case(2, [40, 100, 7, 33], lay_s, lay_d, n_heads=10, d=64,
                                           B=16, layers=7, seed=unroll)
