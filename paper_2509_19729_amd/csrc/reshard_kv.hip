@@ -214,6 +214,95 @@ kv_regroup_kernel(const KVArgs a, const int32_t* __restrict__ ws) {
   }
 }
 
+// Layout-converting regroup through LDS (token-first <-> header-centric).
+//
+// Between the two layouts a block is transposed at the granularity of one head vector
+// (d * elem_bytes bytes): in the token-first block the heads of a token are adjacent, in
+// the header-centric block the tokens of a head are.  Gathering directly, one side of
+// the copy is touched in pieces of one head vector; when that is less than a 128-byte
+// cache line (d = 32 at 16 bits: 64 bytes) every line is fetched twice (FETCH_SIZE
+// doubles, the rate drops to about 4 TB/s).  Here a workgroup owns a tile of
+// (tile_tokens x tile_heads) head vectors of one K-or-V plane: it reads the tile in the
+// source's storage order, parks it in LDS, and writes it in the destination's order, so
+// both sides see runs of tile_heads (or tile_tokens) head vectors.
+struct KVStagedGeom {
+  uint32_t tile_tokens, tile_heads;  // tile extent; tile_tokens divides block_tokens
+  uint32_t block_tokens;
+  uint32_t tile_vecs;                // tile_tokens * tile_heads * dv
+  FastDiv token_groups;              // block_tokens / tile_tokens
+  FastDiv fd_tile_tokens, fd_tile_heads;
+};
+
+template <int LAYOUT>
+__device__ __forceinline__ void staged_split(uint32_t e, const KVStagedGeom& g, uint32_t& t,
+                                             uint32_t& h) {
+  if (LAYOUT == AMOEBA_KV_TOKEN_MAJOR) {  // storage order: token outer, head inner
+    t = fd_div(e, g.fd_tile_heads);
+    h = e - t * g.tile_heads;
+  } else {                                // head outer, token inner
+    h = fd_div(e, g.fd_tile_tokens);
+    t = e - h * g.tile_tokens;
+  }
+}
+
+template <int LAYOUT>
+__device__ __forceinline__ uint32_t block_vec(uint32_t h, uint32_t c, uint32_t t, uint32_t x,
+                                              uint32_t heads, uint32_t B, uint32_t dv) {
+  if (LAYOUT == AMOEBA_KV_HEAD_MAJOR) return ((h * 2 + c) * B + t) * dv + x;
+  return ((c * B + t) * heads + h) * dv + x;
+}
+
+template <int SL, int DL, bool NT>
+__global__ void __launch_bounds__(kThreads)
+kv_regroup_staged_kernel(const KVArgs a, const KVStagedGeom g, const int32_t* __restrict__ ws) {
+  extern __shared__ u32x4 tile_lds[];  // [tile_tokens][tile_heads][dv]
+  const uint32_t tid = threadIdx.x;
+  const uint32_t layer = blockIdx.y;
+  const uint32_t total = (uint32_t)ws[kWsTotal];
+  const int32_t* __restrict__ worklist = ws + kWsHeader + a.num_seqs;
+  const uint32_t n_items = total * a.tiles_per_block.d;
+  const uint32_t dv = a.dv.d, B = g.block_tokens;
+
+  for (uint32_t w = blockIdx.x; w < n_items; w += gridDim.x) {
+    const uint32_t b = fd_div(w, a.tiles_per_block);
+    const uint32_t tile = w - b * a.tiles_per_block.d;
+    const int32_t sb = worklist[b];
+    // tile -> (head group, K/V plane, token group), token group fastest
+    const uint32_t r = fd_div(tile, g.token_groups);
+    const uint32_t t0 = (tile - r * g.token_groups.d) * g.tile_tokens;
+    const uint32_t c = r & 1, h0 = (r >> 1) * g.tile_heads;
+    const uint64_t soff = uint64_t(layer) * a.src_layer_stride + uint64_t(sb) * a.src_block_bytes;
+    char* dp = a.dst + uint64_t(layer) * a.dst_layer_stride + uint64_t(b) * a.dst_block_bytes;
+
+    for (uint32_t v = tid; v < g.tile_vecs; v += kThreads) {  // source order -> LDS
+      const uint32_t e = fd_div(v, a.dv), x = v - e * dv;
+      uint32_t t, h;
+      staged_split<SL>(e, g, t, h);
+      const uint32_t hp = h0 + h;
+      if (hp < a.heads_dst.d && sb >= 0) {
+        const uint32_t hg = a.head0 + hp;
+        const uint32_t s = fd_div(hg, a.heads_src);
+        const uint32_t hs = hg - s * a.heads_src.d;
+        const char* pool = (a.n_src <= 2) ? ((s == a.rank_lo) ? a.src_lo : a.src_hi) : a.src[s];
+        const uint32_t sv = block_vec<SL>(hs, c, t0 + t, x, a.heads_src.d, B, dv);
+        tile_lds[(t * g.tile_heads + h) * dv + x] = ld<NT, u32x4>(pool + soff + uint64_t(sv) * 16);
+      }
+    }
+    __syncthreads();
+    for (uint32_t v = tid; v < g.tile_vecs; v += kThreads) {  // LDS -> destination order
+      const uint32_t e = fd_div(v, a.dv), x = v - e * dv;
+      uint32_t t, h;
+      staged_split<DL>(e, g, t, h);
+      const uint32_t hp = h0 + h;
+      if (hp < a.heads_dst.d && sb >= 0) {
+        const uint32_t dvi = block_vec<DL>(hp, c, t0 + t, x, a.heads_dst.d, B, dv);
+        st<NT, u32x4>(dp + uint64_t(dvi) * 16, tile_lds[(t * g.tile_heads + h) * dv + x]);
+      }
+    }
+    __syncthreads();  // the next tile reuses the LDS buffer
+  }
+}
+
 namespace {
 
 template <int SL, int DL, int VEC, int THREADS, int UNROLL>
@@ -321,6 +410,74 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
     if (!hip_ok("kv table kernel launch failed", err)) return AMOEBA_ERR_HIP;
   }
   // 3. regroup
+  // Converting between the layouts goes through LDS when one head vector is shorter than
+  // a cache line (see kv_regroup_staged_kernel); with 256-byte head vectors the direct
+  // gather already moves whole lines and measured the same or faster.
+  const bool convert = s.kv_layout_src != s.kv_layout_dst;
+  const bool want_staged = p->tune.kv_staged == 1 || (p->tune.kv_staged == 0 && head_vec_bytes < 128);
+  if (convert && vec == 16 && want_staged && head_vec_bytes <= 4096) {
+    const uint32_t dv = uint32_t(head_vec_bytes / 16), B = uint32_t(s.kv_block_tokens);
+    const uint32_t target = 4096u * uint32_t(unroll == 1 ? 2 : unroll);  // tile bytes aimed at
+    uint32_t tt = std::max<uint32_t>(1, 1024u / uint32_t(head_vec_bytes));
+    tt = std::min(tt, B);
+    while (B % tt) --tt;  // tokens per tile divide the block
+    uint32_t th = std::max<uint32_t>(1, target / (tt * uint32_t(head_vec_bytes)));
+    th = std::min<uint32_t>(th, uint32_t(p->heads_dst));
+    KVStagedGeom g;
+    g.tile_tokens = tt;
+    g.tile_heads = th;
+    g.block_tokens = B;
+    g.tile_vecs = tt * th * dv;
+    g.token_groups = make_fastdiv(B / tt);
+    g.fd_tile_tokens = make_fastdiv(tt);
+    g.fd_tile_heads = make_fastdiv(th);
+    const uint64_t head_groups = (uint64_t(p->heads_dst) + th - 1) / th;
+    const uint64_t tiles_per_block = head_groups * 2 * (B / tt);
+    const uint64_t max_items = uint64_t(s.dst_pool_blocks) * tiles_per_block;
+    if (max_items >= (uint64_t(1) << 32) - (1 << 24) || s.kv_layers > 65535) {
+      *err = "KV pool too large for 32-bit work indexing";
+      return AMOEBA_ERR_INVALID_ARG;
+    }
+    if (max_items == 0 || cells == 0) return AMOEBA_OK;
+    a.dst = static_cast<char*>(dst_blocks);
+    a.ws = p->workspace;
+    a.src_layer_stride = src_layer;
+    a.dst_layer_stride = dst_layer;
+    a.src_block_bytes = uint64_t(p->block_bytes_src);
+    a.dst_block_bytes = uint64_t(p->block_bytes_dst);
+    a.num_seqs = uint32_t(s.num_seqs);
+    a.block_vecs = uint32_t(uint64_t(p->block_bytes_dst) / 16);
+    a.tiles_per_block = make_fastdiv(uint32_t(tiles_per_block));
+    a.head0 = uint32_t(p->rp * p->heads_dst);
+    a.rank_lo = a.head0 / uint32_t(p->heads_src);
+    a.rank_hi = (a.head0 + uint32_t(p->heads_dst) - 1) / uint32_t(p->heads_src);
+    a.n_src = a.rank_hi - a.rank_lo + 1;
+    a.src_lo = a.src[a.rank_lo];
+    a.src_hi = a.src[a.rank_hi];
+    a.heads_src = make_fastdiv(uint32_t(p->heads_src));
+    a.heads_dst = make_fastdiv(uint32_t(p->heads_dst));
+    a.dv = make_fastdiv(dv);
+    a.head_vecs = make_fastdiv(2u * B * dv);
+    uint64_t grid = std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 27) / uint64_t(s.kv_layers));
+    if (p->tune.kv_grid > 0) grid = uint64_t(p->tune.kv_grid);
+    grid = std::min<uint64_t>(grid, max_items);
+    const dim3 gr(uint32_t(grid), uint32_t(s.kv_layers));
+    const size_t lds = size_t(g.tile_vecs) * 16;
+    const bool src_hm = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR;
+#define AMOEBA_STAGED(SL, DL, NTV)                                                             \
+  hipLaunchKernelGGL((kv_regroup_staged_kernel<SL, DL, NTV>), gr, dim3(kThreads), lds, stream, \
+                     a, g, a.ws)
+    if (src_hm) {
+      if (nt) AMOEBA_STAGED(AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR, true);
+      else AMOEBA_STAGED(AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR, false);
+    } else {
+      if (nt) AMOEBA_STAGED(AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR, true);
+      else AMOEBA_STAGED(AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR, false);
+    }
+#undef AMOEBA_STAGED
+    if (!hip_ok("kv staged regroup kernel launch failed", err)) return AMOEBA_ERR_HIP;
+    return AMOEBA_OK;
+  }
   const uint64_t block_vecs = uint64_t(p->block_bytes_dst) / vec;
   const uint64_t tile_vecs = uint64_t(threads) * unroll;
   const uint64_t tiles_per_block = (block_vecs + tile_vecs - 1) / tile_vecs;

@@ -223,6 +223,26 @@ def test_kv_blocks_of_several_tiles_and_launch_shapes(unroll, threads, grid):
         check_kv(cfg, 2, 5, 3, pools, table, lens, tune=tune)
 
 
+@pytest.mark.parametrize("staged", [1, 2])
+@pytest.mark.parametrize("n_heads,d,B,k,kp,rp", [
+    (10, 64, 16, 2, 1, 0),    # 10 target heads: ragged last head group, two source ranks
+    (10, 64, 16, 2, 5, 3),    # 2 target heads out of 5 per source rank
+    (8, 32, 16, 1, 2, 1),     # 64-byte head vectors, the tiny config's geometry
+    (6, 8, 12, 3, 1, 0),      # 16-byte head vectors, block of 12 tokens, three source ranks
+    (4, 128, 16, 4, 1, 0),    # 256-byte head vectors, four source ranks (table lookup path)
+    (12, 256, 8, 2, 3, 1),    # 512-byte head vectors, TP degrees that do not divide each other
+])
+def test_kv_layout_conversion_staged_and_direct(staged, n_heads, d, B, k, kp, rp):
+    """Token-first <-> header-centric through the LDS-staged kernel (staged=1) and through
+    the direct gather (staged=2): both must equal the oracle."""
+    for lay_s, lay_d in [(TM, HM), (HM, TM)]:
+        cfg, pools, table, lens = kv_case(k, [40, 100, 7, 33, 0, 16], lay_s, lay_d,
+                                          n_heads=n_heads, d=d, B=B, layers=3, seed=d + staged)
+        check_kv(cfg, k, kp, rp, pools, table, lens, tune={ab.TUNE_KV_STAGED: staged})
+        check_kv(cfg, k, kp, rp, pools, table, lens,
+                 tune={ab.TUNE_KV_STAGED: staged, ab.TUNE_KV_GRID: 5, ab.TUNE_KV_UNROLL: 4})
+
+
 def test_kv_more_than_one_scan_chunk():
     """3000 sequences: the scan carries its running total across chunks of 1024."""
     rng = np.random.default_rng(3)
