@@ -155,10 +155,49 @@ int amoeba_reshard_kv(const amoeba_plan_t* plan, const void* const* src_blocks,
  * if the copy back fails).  total_blocks (may be NULL) receives sum_i nb_i. */
 int amoeba_kv_status(const amoeba_plan_t* plan, void* stream, int64_t* total_blocks);
 
+/*
+ * In-place merge of m = dst_tp / src_tp instances into one (Sec. 3.1: the paper's
+ * 4 x TP1 -> TP4 scenario, base solution + Improvement 1 "in-place migration with
+ * header-centric layout").  Each instance runs at TP = src_tp with its own sequences,
+ * block table and pools.  Target rank dst_rank = s*m + g is hosted where rank s of
+ * instance g was and reuses that rank's pool:
+ *   local_pool       : DEVICE, in/out.  In : [kv_layers][src_pool_blocks][block(src_tp)].
+ *                      Out: the same bytes read as [kv_layers][src_pool_blocks*m][block(dst_tp)]
+ *                      ("block reshaping": old block b = new blocks b*m .. b*m+m-1, one per
+ *                      m-th of the heads).  Heads of local sequences that dst_rank keeps are
+ *                      not moved; the sub-blocks it gives away are overwritten by the heads
+ *                      it receives: new block b*m + g2 <- heads of dst_rank in block b of
+ *                      remote_pools[g2], for every block b of every sequence of instance g2.
+ *   remote_pools     : HOST array of m DEVICE pointers, entry g2 = pool of rank s of
+ *                      instance g2 (same geometry, read only; entry g is ignored).
+ *   src_block_tables : HOST array of m DEVICE int32 [num_seqs][max_blocks_per_seq].
+ *   seq_lens         : HOST array of m DEVICE int32 [num_seqs].
+ *   dst_block_tables : DEVICE int32 [m*num_seqs][max_blocks_per_seq], instance-major;
+ *                      entry = old id * m + instance, -1 padded; identical for every dst_rank.
+ * The plan must have kv_layout_src = kv_layout_dst = AMOEBA_KV_HEAD_MAJOR and
+ * amoeba_plan_merge_factor(plan) = m >= 2 (dst_pool_blocks is not used).  Enqueues three
+ * kernels, no host synchronisation, no extra device memory beyond the plan's workspace
+ * (4*(8 + m*num_seqs + 2*m*src_pool_blocks) bytes).  Device-found conditions are read
+ * with amoeba_merge_kv_status(): AMOEBA_ERR_OVERFLOW (negative length / row too short:
+ * nothing written, table all -1), AMOEBA_ERR_BLOCK_ID (an id outside the pool: entry -1,
+ * block skipped).  Calls on one plan must not overlap in time.
+ */
+int amoeba_merge_kv_inplace(const amoeba_plan_t* plan, void* local_pool,
+                            const void* const* remote_pools,
+                            const int32_t* const* src_block_tables,
+                            const int32_t* const* seq_lens, int32_t* dst_block_tables,
+                            void* stream);
+
+/* Like amoeba_kv_status() for the last amoeba_merge_kv_inplace() on this plan;
+ * remote_blocks (may be NULL) receives the blocks copied per layer. */
+int amoeba_merge_kv_status(const amoeba_plan_t* plan, void* stream, int64_t* remote_blocks);
+
 /* ---- queries (host only) ------------------------------------------------- */
 
 /* Bytes of one rank's weight shard, all layers.  side: 0 = source TP, 1 = target TP. */
 size_t amoeba_plan_shard_bytes(const amoeba_plan_t* plan, int side);
+/* m if the plan can be used with amoeba_merge_kv_inplace(), else 0. */
+int amoeba_plan_merge_factor(const amoeba_plan_t* plan);
 /* Bytes of one KV block on one rank. */
 size_t amoeba_plan_kv_block_bytes(const amoeba_plan_t* plan, int side);
 /* Bit s set: source rank s holds weights the target rank needs. */

@@ -104,6 +104,13 @@ def lib():
                                     ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p,
                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                     ctypes.POINTER(ctypes.c_int64)]
+        L.ao_merge_kv_inplace.restype = ctypes.c_int
+        L.ao_merge_kv_inplace.argtypes = [ctypes.POINTER(_KV), ctypes.c_int, ctypes.c_int,
+                                          ctypes.c_int, ctypes.c_void_p,
+                                          ctypes.POINTER(ctypes.c_void_p),
+                                          ctypes.POINTER(ctypes.c_void_p),
+                                          ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p,
+                                          ctypes.POINTER(ctypes.c_int64)]
         _lib = L
     return _lib
 
@@ -166,3 +173,24 @@ def reshard_kv(c: KV, src_tp: int, dst_tp: int, dst_rank: int, src_pools, src_ta
                              src_table.ctypes.data, seq_lens.ctypes.data, dst_pool.ctypes.data,
                              dst_table.ctypes.data, ctypes.byref(total))
     return int(st), dst_table, int(total.value)
+
+
+def merge_kv_inplace(c: KV, src_tp: int, m: int, dst_rank: int, local_pool, remote_pools,
+                     src_tables, seq_lens, dst_table=None):
+    """In-place merge of m instances (header-centric).  local_pool [kv_layers, P, block(src_tp)]
+    is modified in place; remote_pools: m arrays (entry dst_rank % m may be None); src_tables,
+    seq_lens: m arrays each.  Returns (status, dst_table [m*S, W], remote_blocks)."""
+    dt = elem_dtype(c.elem_bytes)
+    assert local_pool.dtype == dt and local_pool.flags["C_CONTIGUOUS"]
+    tabs = [np.ascontiguousarray(t, dtype=np.int32) for t in src_tables]
+    lens = [np.ascontiguousarray(x, dtype=np.int32) for x in seq_lens]
+    if dst_table is None:
+        dst_table = np.full((m * c.num_seqs, c.max_blocks_per_seq), -7, dtype=np.int32)
+    pools, _k1 = _ptr_array(remote_pools, max(m, 1), dt)
+    tptr, _k2 = _ptr_array(tabs, max(m, 1), np.int32)
+    lptr, _k3 = _ptr_array(lens, max(m, 1), np.int32)
+    n = ctypes.c_int64(-1)
+    st = lib().ao_merge_kv_inplace(ctypes.byref(c._c()), src_tp, m, dst_rank,
+                                   local_pool.ctypes.data, pools, tptr, lptr,
+                                   dst_table.ctypes.data, ctypes.byref(n))
+    return int(st), dst_table, int(n.value)

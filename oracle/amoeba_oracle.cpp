@@ -208,6 +208,51 @@ int reshard_kv_t(const ao_kv* c, int k, int kp, int rp, const void* const* src_v
   return bad_id ? AO_ERR_BLOCK_ID : AO_OK;
 }
 
+template <typename E>
+int merge_kv_inplace_t(const ao_kv* c, int k, int m, int rp, void* local_v,
+                       const void* const* remote_v, const int32_t* const* tables,
+                       const int32_t* const* lens, int32_t* dst_table, int64_t* remote_out) {
+  const int64_t S = c->num_seqs, W = c->max_blocks_per_seq, B = c->block_tokens, d = c->head_dim;
+  const int64_t P = c->src_pool_blocks;
+  const int64_t g = rp % m;                            // instance hosted here
+  const int64_t heads_new = c->n_kv_heads / ((int64_t)k * m);
+  const int64_t sub = heads_new * 2 * B * d;           // elements of one new (sub-)block
+  const int64_t old_block = sub * m;
+  if (remote_out) *remote_out = 0;
+  for (int64_t i = 0; i < (int64_t)m * S * W; ++i) dst_table[i] = -1;
+
+  for (int64_t g2 = 0; g2 < m; ++g2)
+    for (int64_t i = 0; i < S; ++i) {
+      const int64_t len = lens[g2][i];
+      if (len < 0 || (len + B - 1) / B > W) return AO_ERR_OVERFLOW;
+    }
+
+  E* local = static_cast<E*>(local_v);
+  bool bad_id = false;
+  int64_t copied = 0;
+  for (int64_t g2 = 0; g2 < m; ++g2) {
+    const E* remote = static_cast<const E*>(remote_v[g2]);
+    for (int64_t i = 0; i < S; ++i) {
+      const int64_t nb = ((int64_t)lens[g2][i] + B - 1) / B;
+      for (int64_t j = 0; j < nb; ++j) {
+        const int64_t b = tables[g2][i * W + j];
+        if (g2 != g) ++copied;                         // counted even if skipped just below
+        if (b < 0 || b >= P) { bad_id = true; continue; }
+        const int64_t id = b * m + g2;                 // reshaped id, same on every rank
+        dst_table[(g2 * S + i) * W + j] = (int32_t)id;
+        if (g2 == g) continue;                         // local heads stay where they are
+        for (int64_t l = 0; l < c->kv_layers; ++l) {
+          const E* from = remote + (l * P + b) * old_block + g * sub;  // heads of r' in block b
+          E* to = local + (l * P * m + id) * sub;
+          for (int64_t x = 0; x < sub; ++x) to[x] = from[x];
+        }
+      }
+    }
+  }
+  if (remote_out) *remote_out = copied;
+  return bad_id ? AO_ERR_BLOCK_ID : AO_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -252,6 +297,32 @@ int ao_reshard_kv(const ao_kv* c, int src_tp, int dst_tp, int dst_rank,
     default:
       return reshard_kv_t<uint32_t>(c, src_tp, dst_tp, dst_rank, src_pools, src_table, seq_lens,
                                     dst_pool, dst_table, total_blocks_out);
+  }
+}
+
+int ao_merge_kv_inplace(const ao_kv* c, int src_tp, int m, int dst_rank, void* local_pool,
+                        const void* const* remote_pools, const int32_t* const* src_tables,
+                        const int32_t* const* seq_lens, int32_t* dst_table,
+                        int64_t* remote_blocks_out) {
+  if (!kv_ok(c) || m < 1 || m > 64 || src_tp < 1 || !divides(src_tp * m, c->n_kv_heads) ||
+      dst_rank < 0 || dst_rank >= src_tp * m || c->layout_src != AO_LAYOUT_HEAD_MAJOR ||
+      c->layout_dst != AO_LAYOUT_HEAD_MAJOR || !local_pool || !remote_pools || !src_tables ||
+      !seq_lens || !dst_table)
+    return AO_ERR_ARG;
+  for (int g2 = 0; g2 < m; ++g2) {
+    if (!src_tables[g2] || !seq_lens[g2]) return AO_ERR_ARG;
+    if (g2 != dst_rank % m && !remote_pools[g2]) return AO_ERR_ARG;
+  }
+  switch (c->elem_bytes) {
+    case 1:
+      return merge_kv_inplace_t<uint8_t>(c, src_tp, m, dst_rank, local_pool, remote_pools,
+                                         src_tables, seq_lens, dst_table, remote_blocks_out);
+    case 2:
+      return merge_kv_inplace_t<uint16_t>(c, src_tp, m, dst_rank, local_pool, remote_pools,
+                                          src_tables, seq_lens, dst_table, remote_blocks_out);
+    default:
+      return merge_kv_inplace_t<uint32_t>(c, src_tp, m, dst_rank, local_pool, remote_pools,
+                                          src_tables, seq_lens, dst_table, remote_blocks_out);
   }
 }
 

@@ -95,6 +95,32 @@ int ao_reshard_kv(const ao_kv* c, int src_tp, int dst_tp, int dst_rank,
                   const int32_t* seq_lens, void* dst_pool, int32_t* dst_table,
                   int64_t* total_blocks_out);
 
+/* In-place merge of m instances running at TP=src_tp into one instance at
+ * TP=src_tp*m, header-centric layout on both sides (Sec. 3.1: every worker keeps,
+ * for its local requests, the heads of its new range where they are; the heads it
+ * gives away leave "bubbles" that are reused by reshaping blocks; Improvement 1).
+ *
+ * Target rank r' = s*m + g is hosted where rank s of instance g was.  local_pool is
+ * that rank's pool [kv_layers][P][block(src_tp)], P = c->src_pool_blocks; afterwards
+ * it is read as [kv_layers][P*m][block(src_tp*m)]: old block b is cut in m sub-blocks
+ * of n_kv/(src_tp*m) heads, sub-block j living at new id b*m + j.
+ *   - a block b of a local sequence keeps sub-block g where it is: new id b*m + g;
+ *   - a block b of a sequence of instance g2 != g gets new id b*m + g2; its heads
+ *     for r' are sub-block g of block b in remote_pools[g2] (rank s of instance g2)
+ *     and are copied there.
+ * No two blocks collide (ids of instance g2 are = g2 mod m) and no extra memory is
+ * needed.  Every instance has c->num_seqs sequences and a table
+ * [num_seqs][max_blocks_per_seq]; dst_table is [m*num_seqs][max_blocks_per_seq] in
+ * instance-major order and is the same for every target rank.  remote_pools[g] is
+ * ignored.  A negative length or a row that is too short gives AO_ERR_OVERFLOW
+ * (nothing written, table all -1); an id outside [0, P) gives a -1 entry, skips the
+ * block and returns AO_ERR_BLOCK_ID.  remote_blocks_out: blocks of remote sequences per
+ * layer (those skipped for a bad id included). */
+int ao_merge_kv_inplace(const ao_kv* c, int src_tp, int m, int dst_rank, void* local_pool,
+                        const void* const* remote_pools, const int32_t* const* src_tables,
+                        const int32_t* const* seq_lens, int32_t* dst_table,
+                        int64_t* remote_blocks_out);
+
 #ifdef __cplusplus
 }
 #endif

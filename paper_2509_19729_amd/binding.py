@@ -32,6 +32,7 @@ EXPORTS = [
     "amoeba_plan_src_rank_mask", "amoeba_plan_kv_rank_mask", "amoeba_plan_tensor_info",
     "amoeba_plan_kv_stride_order", "amoeba_plan_num_segments", "amoeba_plan_segment",
     "amoeba_plan_tune", "amoeba_copy_baseline", "amoeba_last_error",
+    "amoeba_merge_kv_inplace", "amoeba_merge_kv_status", "amoeba_plan_merge_factor",
 ]
 
 
@@ -111,6 +112,13 @@ def lib() -> ctypes.CDLL:
     L.amoeba_plan_tune.argtypes = [vp, i32, i32]
     L.amoeba_copy_baseline.restype = i32
     L.amoeba_copy_baseline.argtypes = [vp, vp, ctypes.c_size_t, i32, i32, i32, vp]
+    L.amoeba_merge_kv_inplace.restype = i32
+    L.amoeba_merge_kv_inplace.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                          ctypes.POINTER(vp), vp, vp]
+    L.amoeba_merge_kv_status.restype = i32
+    L.amoeba_merge_kv_status.argtypes = [vp, vp, ctypes.POINTER(i64)]
+    L.amoeba_plan_merge_factor.restype = i32
+    L.amoeba_plan_merge_factor.argtypes = [vp]
     L.amoeba_last_error.restype = ctypes.c_char_p
     L.amoeba_last_error.argtypes = []
     _lib = L
@@ -268,3 +276,25 @@ def amoeba_copy_baseline(dst, src, nbytes: int, unroll: int = 4, grid: int = 0,
                                     _stream_handle(stream))
     if rc != OK:
         raise AmoebaError(rc, amoeba_last_error())
+
+
+def amoeba_plan_merge_factor(plan: Plan) -> int:
+    return int(lib().amoeba_plan_merge_factor(plan.handle))
+
+
+def amoeba_merge_kv_inplace(plan: Plan, local_pool, remote_pools, src_block_tables, seq_lens,
+                            dst_block_tables, stream=None, check: bool = True) -> int:
+    m = max(amoeba_plan_merge_factor(plan), 1)
+    rc = lib().amoeba_merge_kv_inplace(plan.handle, _ptr(local_pool), _ptr_array(remote_pools, m),
+                                       _ptr_array(src_block_tables, m), _ptr_array(seq_lens, m),
+                                       _ptr(dst_block_tables), _stream_handle(stream))
+    if check and rc != OK:
+        raise AmoebaError(rc, amoeba_last_error())
+    return rc
+
+
+def amoeba_merge_kv_status(plan: Plan, stream=None):
+    """Synchronises the stream; returns (status, remote_blocks_per_layer)."""
+    total = ctypes.c_int64(0)
+    rc = lib().amoeba_merge_kv_status(plan.handle, _stream_handle(stream), ctypes.byref(total))
+    return rc, int(total.value)

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libamoeba.so")
 SOURCES = ["api.cpp", "plan.cpp", "reshard_weights.hip", "reshard_kv.hip",
-           "copy_baseline.hip"]
+           "copy_baseline.hip", "merge_kv.hip"]
 
 
 def hipcc() -> str:

@@ -20,6 +20,36 @@ void set_error(const std::string& msg) { g_last_error = msg; }
 
 using amoeba::set_error;
 
+namespace {
+
+// Shared by the two status calls: copies the 2-word header back and decodes the flags.
+int read_status(const char* who, const int32_t* ws, void* stream, int64_t* total) {
+  int32_t head[2] = {0, 0};
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t rc = hipMemcpyAsync(head, ws, sizeof(head), hipMemcpyDeviceToHost, st);
+  if (rc == hipSuccess) rc = hipStreamSynchronize(st);
+  if (rc != hipSuccess) {
+    set_error(std::string(who) + ": " + hipGetErrorString(rc));
+    return AMOEBA_ERR_HIP;
+  }
+  if (total) *total = head[amoeba::kWsTotal];
+  const int e = head[amoeba::kWsError];
+  if (e & (amoeba::kErrNegativeLen | amoeba::kErrRowTooShort | amoeba::kErrPoolTooSmall)) {
+    set_error(std::string(who) + ": " +
+              ((e & amoeba::kErrNegativeLen) ? "negative sequence length; " : "") +
+              ((e & amoeba::kErrRowTooShort) ? "a sequence needs more blocks than a table row holds; " : "") +
+              ((e & amoeba::kErrPoolTooSmall) ? "destination pool too small; " : ""));
+    return AMOEBA_ERR_OVERFLOW;
+  }
+  if (e & amoeba::kErrBlockId) {
+    set_error(std::string(who) + ": a source block id lies outside the source pool");
+    return AMOEBA_ERR_BLOCK_ID;
+  }
+  return AMOEBA_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* amoeba_last_error(void) { return g_last_error.c_str(); }
@@ -37,6 +67,8 @@ amoeba_plan_t* amoeba_plan(const amoeba_model_shape* shape, int src_tp, int dst_
   p->device = -1;
   p->n_cu = 0;
   p->workspace = nullptr;
+  p->merge_workspace = nullptr;
+  p->merge_workspace_bytes = 0;
   p->workspace_bytes = 0;
   int n_dev = 0;
   if (hipGetDeviceCount(&n_dev) == hipSuccess && n_dev > 0) {
@@ -58,6 +90,23 @@ amoeba_plan_t* amoeba_plan(const amoeba_model_shape* shape, int src_tp, int dst_
       p->device = dev;
       p->workspace = static_cast<int32_t*>(ws);
       p->workspace_bytes = bytes;
+      if (p->merge_factor >= 2) {
+        const size_t m = size_t(p->merge_factor);
+        const size_t mbytes =
+            sizeof(int32_t) * (size_t(amoeba::kWsHeader) + m * size_t(p->shape.num_seqs) +
+                               2 * m * size_t(p->shape.src_pool_blocks));
+        void* mws = nullptr;
+        const hipError_t mrc = hipMalloc(&mws, mbytes);
+        if (mrc != hipSuccess) {
+          set_error(std::string("amoeba_plan: merge workspace allocation failed: ") +
+                    hipGetErrorString(mrc));
+          (void)hipFree(ws);
+          delete p;
+          return nullptr;
+        }
+        p->merge_workspace = static_cast<int32_t*>(mws);
+        p->merge_workspace_bytes = mbytes;
+      }
     }
   } else {
     (void)hipGetLastError();  // no GPU: host-side planning only
@@ -69,6 +118,7 @@ amoeba_plan_t* amoeba_plan(const amoeba_model_shape* shape, int src_tp, int dst_
 void amoeba_plan_destroy(amoeba_plan_t* plan) {
   if (!plan) return;
   if (plan->workspace) (void)hipFree(plan->workspace);
+  if (plan->merge_workspace) (void)hipFree(plan->merge_workspace);
   delete plan;
 }
 
@@ -105,29 +155,35 @@ int amoeba_kv_status(const amoeba_plan_t* plan, void* stream, int64_t* total_blo
     set_error("amoeba_kv_status: NULL plan or no device workspace");
     return AMOEBA_ERR_INVALID_ARG;
   }
-  int32_t head[2] = {0, 0};
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  hipError_t rc = hipMemcpyAsync(head, plan->workspace, sizeof(head), hipMemcpyDeviceToHost, st);
-  if (rc == hipSuccess) rc = hipStreamSynchronize(st);
-  if (rc != hipSuccess) {
-    set_error(std::string("amoeba_kv_status: ") + hipGetErrorString(rc));
-    return AMOEBA_ERR_HIP;
-  }
-  if (total_blocks) *total_blocks = head[amoeba::kWsTotal];
-  const int e = head[amoeba::kWsError];
-  if (e & (amoeba::kErrNegativeLen | amoeba::kErrRowTooShort | amoeba::kErrPoolTooSmall)) {
-    set_error(std::string("amoeba_kv_status: ") +
-              ((e & amoeba::kErrNegativeLen) ? "negative sequence length; " : "") +
-              ((e & amoeba::kErrRowTooShort) ? "a sequence needs more blocks than a table row holds; " : "") +
-              ((e & amoeba::kErrPoolTooSmall) ? "destination pool too small; " : ""));
-    return AMOEBA_ERR_OVERFLOW;
-  }
-  if (e & amoeba::kErrBlockId) {
-    set_error("amoeba_kv_status: a source block id lies outside the source pool");
-    return AMOEBA_ERR_BLOCK_ID;
-  }
-  return AMOEBA_OK;
+  return read_status("amoeba_kv_status", plan->workspace, stream, total_blocks);
 }
+
+int amoeba_merge_kv_inplace(const amoeba_plan_t* plan, void* local_pool,
+                            const void* const* remote_pools,
+                            const int32_t* const* src_block_tables,
+                            const int32_t* const* seq_lens, int32_t* dst_block_tables,
+                            void* stream) {
+  if (!plan) {
+    set_error("amoeba_merge_kv_inplace: NULL plan");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  std::string err;
+  const int rc = amoeba::launch_merge_kv_inplace(plan, local_pool, remote_pools, src_block_tables,
+                                                 seq_lens, dst_block_tables,
+                                                 static_cast<hipStream_t>(stream), &err);
+  if (rc != AMOEBA_OK) set_error("amoeba_merge_kv_inplace: " + err);
+  return rc;
+}
+
+int amoeba_merge_kv_status(const amoeba_plan_t* plan, void* stream, int64_t* remote_blocks) {
+  if (!plan || !plan->merge_workspace) {
+    set_error("amoeba_merge_kv_status: NULL plan or no merge workspace");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  return read_status("amoeba_merge_kv_status", plan->merge_workspace, stream, remote_blocks);
+}
+
+int amoeba_plan_merge_factor(const amoeba_plan_t* plan) { return plan ? plan->merge_factor : 0; }
 
 size_t amoeba_plan_shard_bytes(const amoeba_plan_t* plan, int side) {
   if (!plan) return 0;

@@ -21,6 +21,12 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
                       const int32_t* src_block_tables, const int32_t* seq_lens, void* dst_blocks,
                       int32_t* dst_block_tables, hipStream_t stream, std::string* err);
 
+int launch_merge_kv_inplace(const amoeba_plan_s* p, void* local_pool,
+                            const void* const* remote_pools,
+                            const int32_t* const* src_block_tables,
+                            const int32_t* const* seq_lens, int32_t* dst_block_tables,
+                            hipStream_t stream, std::string* err);
+
 int launch_copy_baseline(void* dst, const void* src, size_t bytes, int unroll, int grid, bool nt,
                          hipStream_t stream, std::string* err);
 

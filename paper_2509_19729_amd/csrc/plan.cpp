@@ -125,6 +125,14 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
   p->kv_rank_mask = 0;
   for (int64_t h = rp * p->heads_dst; h < (rp + 1) * p->heads_dst; ++h)
     p->kv_rank_mask |= 1u << (h / p->heads_src);
+
+  // In-place merge of m = k'/k instances (Sec. 3.1, Improvement 1) needs the
+  // header-centric block on both sides, where a rank's new head range is one
+  // contiguous sub-block, and reshaped ids b*m + g that still fit an int32.
+  p->merge_factor = 0;
+  if (kp % k == 0 && kp / k >= 2 && s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR &&
+      s.kv_layout_dst == AMOEBA_KV_HEAD_MAJOR && s.src_pool_blocks * (kp / k) <= INT32_MAX)
+    p->merge_factor = kp / k;
   return true;
 }
 

@@ -51,6 +51,10 @@ struct amoeba_plan_s {
   int n_cu;             // compute units of that device
   int32_t* workspace;   // [8 header][num_seqs bases][dst_pool_blocks source ids]
   size_t workspace_bytes;
+  // in-place instance merge: m = dst_tp / src_tp when the plan qualifies, else 0
+  int merge_factor;
+  int32_t* merge_workspace;  // [8 header][m * num_seqs bases][P*m source ids][P*m instances]
+  size_t merge_workspace_bytes;
   amoeba::Tuning tune;
 };
 
