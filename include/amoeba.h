@@ -78,7 +78,13 @@ enum {
   AMOEBA_TUNE_KV_UNROLL = 4,   /* vectors per lane per tile: 1, 2 or 4                       */
   AMOEBA_TUNE_KV_THREADS = 5,  /* lanes per workgroup: 64 or 256                             */
   AMOEBA_TUNE_NONTEMPORAL = 6, /* 1: streaming (nt) loads/stores, 2: plain                   */
-  AMOEBA_TUNE_KV_STAGED = 7    /* 1: LDS-staged layout-converting regroup, 2: direct         */
+  AMOEBA_TUNE_KV_STAGED = 7,   /* 1: LDS-staged layout-converting regroup, 2: direct         */
+  AMOEBA_TUNE_KV_BLOCKS_HINT = 8 /* upper bound on the blocks the next KV calls will move (the
+                                  host scheduler knows it; the library only sees device-side
+                                  lengths).  Sizes the grid: without it the grid covers the
+                                  pool's capacity and idle workgroups cost dispatch time when
+                                  the pool is far from full.  A hint that is too small is
+                                  still correct (workgroups stride), only slower.            */
 };
 
 /* Caller-owned POD; amoeba_plan() copies it. */
@@ -177,7 +183,8 @@ int amoeba_kv_status(const amoeba_plan_t* plan, void* stream, int64_t* total_blo
  * The plan must have kv_layout_src = kv_layout_dst = AMOEBA_KV_HEAD_MAJOR and
  * amoeba_plan_merge_factor(plan) = m >= 2 (dst_pool_blocks is not used).  Enqueues three
  * kernels, no host synchronisation, no extra device memory beyond the plan's workspace
- * (4*(8 + m*num_seqs + 2*m*src_pool_blocks) bytes).  Device-found conditions are read
+ * (about 8*m*src_pool_blocks bytes: a flag and a work-list entry per new block id).
+ * Device-found conditions are read
  * with amoeba_merge_kv_status(): AMOEBA_ERR_OVERFLOW (negative length / row too short:
  * nothing written, table all -1), AMOEBA_ERR_BLOCK_ID (an id outside the pool: entry -1,
  * block skipped).  Calls on one plan must not overlap in time.

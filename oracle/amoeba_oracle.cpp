@@ -236,11 +236,11 @@ int merge_kv_inplace_t(const ao_kv* c, int k, int m, int rp, void* local_v,
       const int64_t nb = ((int64_t)lens[g2][i] + B - 1) / B;
       for (int64_t j = 0; j < nb; ++j) {
         const int64_t b = tables[g2][i * W + j];
-        if (g2 != g) ++copied;                         // counted even if skipped just below
         if (b < 0 || b >= P) { bad_id = true; continue; }
         const int64_t id = b * m + g2;                 // reshaped id, same on every rank
         dst_table[(g2 * S + i) * W + j] = (int32_t)id;
         if (g2 == g) continue;                         // local heads stay where they are
+        ++copied;
         for (int64_t l = 0; l < c->kv_layers; ++l) {
           const E* from = remote + (l * P + b) * old_block + g * sub;  // heads of r' in block b
           E* to = local + (l * P * m + id) * sub;

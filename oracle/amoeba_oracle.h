@@ -114,8 +114,7 @@ int ao_reshard_kv(const ao_kv* c, int src_tp, int dst_tp, int dst_rank,
  * instance-major order and is the same for every target rank.  remote_pools[g] is
  * ignored.  A negative length or a row that is too short gives AO_ERR_OVERFLOW
  * (nothing written, table all -1); an id outside [0, P) gives a -1 entry, skips the
- * block and returns AO_ERR_BLOCK_ID.  remote_blocks_out: blocks of remote sequences per
- * layer (those skipped for a bad id included). */
+ * block and returns AO_ERR_BLOCK_ID.  remote_blocks_out: blocks copied per layer. */
 int ao_merge_kv_inplace(const ao_kv* c, int src_tp, int m, int dst_rank, void* local_pool,
                         const void* const* remote_pools, const int32_t* const* src_tables,
                         const int32_t* const* seq_lens, int32_t* dst_table,

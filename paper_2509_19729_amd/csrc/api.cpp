@@ -91,10 +91,10 @@ amoeba_plan_t* amoeba_plan(const amoeba_model_shape* shape, int src_tp, int dst_
       p->workspace = static_cast<int32_t*>(ws);
       p->workspace_bytes = bytes;
       if (p->merge_factor >= 2) {
-        const size_t m = size_t(p->merge_factor);
         const size_t mbytes =
-            sizeof(int32_t) * (size_t(amoeba::kWsHeader) + m * size_t(p->shape.num_seqs) +
-                               2 * m * size_t(p->shape.src_pool_blocks));
+            sizeof(int32_t) * amoeba::merge_workspace_ints(p->shape.num_seqs,
+                                                           p->shape.src_pool_blocks,
+                                                           p->merge_factor);
         void* mws = nullptr;
         const hipError_t mrc = hipMalloc(&mws, mbytes);
         if (mrc != hipSuccess) {
@@ -271,6 +271,7 @@ int amoeba_plan_tune(amoeba_plan_t* plan, int knob, int value) {
     case AMOEBA_TUNE_KV_THREADS: plan->tune.kv_threads = value; break;
     case AMOEBA_TUNE_NONTEMPORAL: plan->tune.nontemporal = value; break;
     case AMOEBA_TUNE_KV_STAGED: plan->tune.kv_staged = value; break;
+    case AMOEBA_TUNE_KV_BLOCKS_HINT: plan->tune.kv_blocks_hint = value; break;
     default: set_error("amoeba_plan_tune: unknown knob"); return AMOEBA_ERR_INVALID_ARG;
   }
   return AMOEBA_OK;

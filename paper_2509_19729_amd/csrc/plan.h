@@ -32,7 +32,7 @@ struct Segment {
 
 struct Tuning {
   int w_grid = 0, w_unroll = 0, w_threads = 0, kv_grid = 0, kv_unroll = 0, kv_threads = 0,
-      nontemporal = 0, kv_staged = 0;
+      nontemporal = 0, kv_staged = 0, kv_blocks_hint = 0;
 };
 
 }  // namespace amoeba
@@ -53,7 +53,7 @@ struct amoeba_plan_s {
   size_t workspace_bytes;
   // in-place instance merge: m = dst_tp / src_tp when the plan qualifies, else 0
   int merge_factor;
-  int32_t* merge_workspace;  // [8 header][m * num_seqs bases][P*m source ids][P*m instances]
+  int32_t* merge_workspace;  // [8 header][chunk counts][P*m flags][P*m work list]
   size_t merge_workspace_bytes;
   amoeba::Tuning tune;
 };

@@ -392,7 +392,12 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
   int unroll = p->tune.kv_unroll, threads = p->tune.kv_threads;
   if (vec != 16 || (unroll != 2 && unroll != 4)) unroll = 1;
   if (vec != 16) threads = 256;
-  else if (threads != 256) threads = 64;  // one wavefront per 1 KiB tile measured best
+  else if (threads != 256 && threads != 64)
+    // One wavefront per 1 KiB tile is fastest when the grid is tight (6.45 vs 6.25 TB/s),
+    // but with the grid sized by the pool's capacity every idle workgroup costs dispatch
+    // time; 4 KiB tiles cut that cost by four.  So: small tiles when the caller bounded the
+    // blocks in use, large ones otherwise.
+    threads = p->tune.kv_blocks_hint > 0 ? 64 : 256;
   const bool nt = p->tune.nontemporal != 2;
 
   // 1. scan
@@ -461,6 +466,9 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
     uint64_t grid = std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 27) / uint64_t(s.kv_layers));
     if (p->tune.kv_grid > 0) grid = uint64_t(p->tune.kv_grid);
     grid = std::min<uint64_t>(grid, max_items);
+    if (p->tune.kv_blocks_hint > 0)
+      grid = std::min<uint64_t>(
+          grid, std::max<uint64_t>(1, uint64_t(p->tune.kv_blocks_hint) * tiles_per_block));
     const dim3 gr(uint32_t(grid), uint32_t(s.kv_layers));
     const size_t lds = size_t(g.tile_vecs) * 16;
     const bool src_hm = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR;
@@ -516,6 +524,9 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
   uint64_t grid = std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 27) / uint64_t(s.kv_layers));
   if (p->tune.kv_grid > 0) grid = uint64_t(p->tune.kv_grid);
   grid = std::min<uint64_t>(grid, max_items);
+  if (p->tune.kv_blocks_hint > 0)
+    grid = std::min<uint64_t>(
+        grid, std::max<uint64_t>(1, uint64_t(p->tune.kv_blocks_hint) * tiles_per_block));
   const dim3 g(uint32_t(grid), uint32_t(s.kv_layers));
   const bool sh = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR, dh = s.kv_layout_dst == AMOEBA_KV_HEAD_MAJOR;
   if (sh && dh)

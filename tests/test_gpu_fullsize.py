@@ -44,6 +44,7 @@ def full():
                           num_seqs=w.num_seqs, max_blocks_per_seq=table.shape[1],
                           src_pool_blocks=src_pool, dst_pool_blocks=total + 64)
     plan = ab.amoeba_plan(shape, w.src_tp, w.dst_tp, w.dst_rank)
+    ab.amoeba_plan_tune(plan, ab.TUNE_KV_BLOCKS_HINT, total)   # as bench.py does
     yield dict(w=w, lens=lens, table=table, src_pool=src_pool, total=total, plan=plan)
     plan.close()
     torch.cuda.empty_cache()

@@ -100,6 +100,11 @@ def test_merge_every_vector_width_and_several_tiles(elem_bytes, d):
     for rp in range(2):
         check_merge(cfg, insts, 2, 1, rp)
     check_merge(cfg, insts, 2, 1, 1, tune={ab.TUNE_KV_GRID: 3, ab.TUNE_NONTEMPORAL: 2})
+    # launch shapes: one or four wavefronts per workgroup, grid bounded by a hint that is
+    # too small (workgroups stride), exact, or absent (grid covers the pool's capacity)
+    for threads, hint in [(64, 1), (256, 1), (64, 9), (256, 9), (0, 0), (0, 9), (256, 0)]:
+        check_merge(cfg, insts, 2, 1, 0,
+                    tune={ab.TUNE_KV_THREADS: threads, ab.TUNE_KV_BLOCKS_HINT: hint})
 
 
 def test_merge_degenerate_and_error_cases():

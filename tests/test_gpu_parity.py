@@ -243,6 +243,18 @@ def test_kv_layout_conversion_staged_and_direct(staged, n_heads, d, B, k, kp, rp
                  tune={ab.TUNE_KV_STAGED: staged, ab.TUNE_KV_GRID: 5, ab.TUNE_KV_UNROLL: 4})
 
 
+@pytest.mark.parametrize("hint", [1, 37, 10_000])
+def test_kv_blocks_in_use_hint_only_changes_the_launch_shape(hint):
+    """The hint bounds the grid; too small a hint makes workgroups stride, too large leaves
+    some idle.  The result is the same either way."""
+    for lay_s, lay_d in [(HM, HM), (TM, HM)]:
+        cfg, pools, table, lens = kv_case(2, [40, 100, 7, 33], lay_s, lay_d, n_heads=10, d=64,
+                                          B=16, layers=3, seed=hint)
+        check_kv(cfg, 2, 1, 0, pools, table, lens, tune={ab.TUNE_KV_BLOCKS_HINT: hint})
+        check_kv(cfg, 2, 5, 2, pools, table, lens,
+                 tune={ab.TUNE_KV_BLOCKS_HINT: hint, ab.TUNE_KV_STAGED: 1})
+
+
 def test_kv_more_than_one_scan_chunk():
     """3000 sequences: the scan carries its running total across chunks of 1024."""
     rng = np.random.default_rng(3)
