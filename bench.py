@@ -36,9 +36,11 @@ def parse():
                     help="KV layers resident per call (0 = all that fit the workload definition)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", default="", help="knob=value,... (AMOEBA_TUNE_* names, lower case)")
-    ap.add_argument("--mode", default="reshard", choices=["reshard", "merge-inplace"],
+    ap.add_argument("--mode", default="reshard", choices=["reshard", "merge-inplace", "merge-naive"],
                     help="reshard: the TP k -> k' hot path (default, the headline metric); "
-                         "merge-inplace: m x TP1 instances -> TP m, KV cache only, in place")
+                         "merge-inplace: m x TP1 instances -> TP m, KV cache only, in place; "
+                         "merge-naive: the same scenario the paper's base way (token-first "
+                         "blocks, every block of every instance moved into a fresh pool)")
     ap.add_argument("--instances", type=int, default=4, help="m for --mode merge-inplace")
     ap.add_argument("--no-hint", action="store_true",
                     help="merge-inplace: do not tell the library how many blocks are in use")
@@ -65,6 +67,8 @@ def main():
     torch.cuda.set_device(0)
     if args.mode == "merge-inplace":
         return merge_inplace(args)
+    if args.mode == "merge-naive":
+        return merge_naive(args)
     w = wl.WORKLOADS[args.workload]
     lay = {"hm": ab.KV_HEAD_MAJOR, "tm": ab.KV_TOKEN_MAJOR}
     lay_s, lay_d = (lay[x] for x in args.layout.split("-"))
@@ -201,6 +205,109 @@ def main():
     print(json.dumps(out), flush=True)
 
 
+def _instances(w, m):
+    """Split the workload's sequences over m TP1 instances, each with its own pool (fullest
+    instance at 90 % occupancy) and a table drawn from a seeded permutation."""
+    import numpy as np
+
+    from paper_2509_19729_amd import workloads as wl
+    lens_all = wl.seq_lens(w)
+    per = [lens_all[g::m] for g in range(m)]
+    S = max(len(x) for x in per)
+    per = [np.concatenate([x, np.zeros(S - len(x), np.int32)]) for x in per]
+    nb = [wl.blocks_per_seq(x, w.block_tokens) for x in per]
+    P = int(np.ceil(max(int(x.sum()) for x in nb) / 0.9))
+    W = max(8, int(-(-max(int(x.max()) for x in nb) // 8) * 8))
+    tables = []
+    for g in range(m):
+        rng = np.random.default_rng(2000 + w.index * 10 + g)
+        ids = rng.permutation(P)[:int(nb[g].sum())]
+        t = np.full((S, W), -1, dtype=np.int32)
+        p = 0
+        for i, n in enumerate(nb[g]):
+            t[i, :n] = ids[p:p + n]
+            p += int(n)
+        tables.append(t)
+    return per, nb, tables, S, P, W
+
+
+def merge_naive(args):
+    """The paper's base solution for the same 4 x TP1 -> TP4 scenario, restated on one GPU:
+    token-first blocks, so the heads a worker keeps are strided pieces inside every block and
+    must be compacted (de-fragmented) just like the heads it receives.  Every block of every
+    instance is therefore regrouped into a fresh pool: m amoeba_reshard_kv calls (TP1 -> TPm,
+    token-first on both sides), one per source instance.  One step = those m calls."""
+    import numpy as np
+    import torch
+
+    from paper_2509_19729_amd import binding as ab
+    from paper_2509_19729_amd import workloads as wl
+
+    w = wl.WORKLOADS[args.workload]
+    m, rank = args.instances, 1 % args.instances
+    per, nb, tables, S, P, W = _instances(w, m)
+    L = args.kv_layers or w.n_layers
+    plans, dsts, outs, srcs = [], [], [], []
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0xA30EBA10 + w.index)
+    for g in range(m):
+        need = int(nb[g].sum())
+        shape = ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim,
+                              w.ffn_dim, elem_bytes=2, kv_block_tokens=w.block_tokens,
+                              kv_layout_src=ab.KV_TOKEN_MAJOR, kv_layout_dst=ab.KV_TOKEN_MAJOR,
+                              kv_layers=L, num_seqs=S, max_blocks_per_seq=W, src_pool_blocks=P,
+                              dst_pool_blocks=need)
+        plan = ab.amoeba_plan(shape, 1, m, rank)
+        ab.amoeba_plan_tune(plan, ab.TUNE_KV_BLOCKS_HINT, need)
+        plans.append(plan)
+        bs, bd = ab.amoeba_plan_kv_block_bytes(plan, 0), ab.amoeba_plan_kv_block_bytes(plan, 1)
+        t = torch.empty(L * P * bs // 2, dtype=torch.bfloat16, device="cuda")
+        for a in range(0, t.numel(), 1 << 28):
+            t[a:a + (1 << 28)].normal_(0.0, 0.02, generator=gen)
+        srcs.append(t)
+        dsts.append(torch.empty(L * need * bd // 2, dtype=torch.bfloat16, device="cuda"))
+        outs.append(torch.empty((S, W), dtype=torch.int32, device="cuda"))
+    tabs_d = [torch.from_numpy(t).cuda() for t in tables]
+    lens_d = [torch.from_numpy(x.astype(np.int32)).cuda() for x in per]
+
+    def step():
+        for g in range(m):
+            ab.amoeba_reshard_kv(plans[g], [srcs[g]], tabs_d[g], lens_d[g], dsts[g], outs[g])
+
+    for _ in range(args.warmup):
+        step()
+    for g in range(m):
+        rc, n = ab.amoeba_kv_status(plans[g])
+        assert rc == ab.OK and n == int(nb[g].sum())
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    dev_ms = e0.elapsed_time(e1) / args.steps
+    total_blocks = sum(int(x.sum()) for x in nb)
+    alg = 2 * total_blocks * bd * L
+    out = {
+        "metric": "naive KV merge (token-first, migrate + de-fragment into a fresh pool), "
+                  "m x TP1 -> TP m, one target rank",
+        "value": round(alg / (ms * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name} KV cache: {m} x TP1 -> TP{m} rank {rank}, {L} layers, "
+                               f"{m} x {S} seqs, {total_blocks} blocks of {w.block_tokens}",
+                   "alg_bytes": alg, "extra_device_memory_bytes": total_blocks * bd * L,
+                   "device_ms": round(dev_ms, 4)},
+    }
+    for pl in plans:
+        pl.close()
+    print(json.dumps(out), flush=True)
+
+
 def merge_inplace(args):
     """m TP1 instances of the workload's model, each serving every m-th sequence of the
     workload with its own pool and table, merged in place into one TP=m instance; one step =
@@ -213,23 +320,7 @@ def merge_inplace(args):
 
     w = wl.WORKLOADS[args.workload]
     m, rank = args.instances, 1 % args.instances
-    lens_all = wl.seq_lens(w)
-    per = [lens_all[g::m] for g in range(m)]
-    S = max(len(x) for x in per)
-    per = [np.concatenate([x, np.zeros(S - len(x), np.int32)]) for x in per]
-    nb = [wl.blocks_per_seq(x, w.block_tokens) for x in per]
-    P = int(np.ceil(max(int(x.sum()) for x in nb) / 0.9))       # fullest instance at 90 %
-    W = max(8, int(-(-max(int(x.max()) for x in nb) // 8) * 8))
-    tables = []
-    for g in range(m):
-        rng = np.random.default_rng(2000 + w.index * 10 + g)
-        ids = rng.permutation(P)[:int(nb[g].sum())]
-        t = np.full((S, W), -1, dtype=np.int32)
-        p = 0
-        for i, n in enumerate(nb[g]):
-            t[i, :n] = ids[p:p + n]
-            p += int(n)
-        tables.append(t)
+    per, nb, tables, S, P, W = _instances(w, m)
     L = args.kv_layers or w.n_layers
     shape = ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim,
                           elem_bytes=2, kv_block_tokens=w.block_tokens, kv_layers=L, num_seqs=S,
