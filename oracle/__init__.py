@@ -49,6 +49,23 @@ class _KV(ctypes.Structure):
                [("src_pool_blocks", ctypes.c_int64), ("dst_pool_blocks", ctypes.c_int64)]
 
 
+class _Pad(ctypes.Structure):
+    _fields_ = [("max_tp", ctypes.c_int32), ("src_padded", ctypes.c_int32),
+                ("dst_padded", ctypes.c_int32), ("page_bytes", ctypes.c_int64)]
+
+
+@dataclass(frozen=True)
+class Pad:
+    """Padded FFN layout parameters (Sec. 3.2, Improvement 1)."""
+    max_tp: int
+    page_bytes: int
+    src_padded: bool = False
+    dst_padded: bool = True
+
+    def _c(self):
+        return _Pad(self.max_tp, int(self.src_padded), int(self.dst_padded), self.page_bytes)
+
+
 @dataclass(frozen=True)
 class Model:
     n_layers: int
@@ -111,6 +128,16 @@ def lib():
                                           ctypes.POINTER(ctypes.c_void_p),
                                           ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p,
                                           ctypes.POINTER(ctypes.c_int64)]
+        L.ao_padded_shard_elems.restype = ctypes.c_int64
+        L.ao_padded_shard_elems.argtypes = [ctypes.POINTER(_Model), ctypes.POINTER(_Pad),
+                                            ctypes.c_int]
+        L.ao_padded_geometry.restype = ctypes.c_int
+        L.ao_padded_geometry.argtypes = [ctypes.POINTER(_Model), ctypes.POINTER(_Pad),
+                                         ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]
+        L.ao_reshard_weights_padded.restype = ctypes.c_int
+        L.ao_reshard_weights_padded.argtypes = [ctypes.POINTER(_Model), ctypes.POINTER(_Pad),
+                                                ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -194,3 +221,28 @@ def merge_kv_inplace(c: KV, src_tp: int, m: int, dst_rank: int, local_pool, remo
                                    local_pool.ctypes.data, pools, tptr, lptr,
                                    dst_table.ctypes.data, ctypes.byref(n))
     return int(st), dst_table, int(n.value)
+
+
+def padded_shard_elems(m: Model, pad: Pad, tp: int) -> int:
+    return int(lib().ao_padded_shard_elems(ctypes.byref(m._c()), ctypes.byref(pad._c()), tp))
+
+
+def padded_geometry(m: Model, pad: Pad, tp: int):
+    """(attn, attn_padded, part, part_padded, stride, layer) in elements at TP=tp."""
+    out = (ctypes.c_int64 * 6)()
+    st = lib().ao_padded_geometry(ctypes.byref(m._c()), ctypes.byref(pad._c()), tp, out)
+    assert st == OK
+    return tuple(int(x) for x in out)
+
+
+def reshard_weights_padded(m: Model, pad: Pad, src_tp: int, dst_tp: int, dst_rank: int,
+                           src_shards, dst=None):
+    """Reshard with either side in the padded layout.  Returns (status, dst)."""
+    dt = elem_dtype(m.elem_bytes)
+    n = padded_shard_elems(m, pad, dst_tp) if pad.dst_padded else shard_elems(m, dst_tp)
+    if dst is None:
+        dst = np.full(max(n, 0), 0xEE, dtype=dt)
+    ptrs, _keep = _ptr_array(src_shards, max(src_tp, 1), dt)
+    st = lib().ao_reshard_weights_padded(ctypes.byref(m._c()), ctypes.byref(pad._c()), src_tp,
+                                         dst_tp, dst_rank, ptrs, dst.ctypes.data)
+    return int(st), dst

@@ -253,6 +253,110 @@ int merge_kv_inplace_t(const ao_kv* c, int k, int m, int rp, void* local_v,
   return bad_id ? AO_ERR_BLOCK_ID : AO_OK;
 }
 
+// ---- padded, partition-major FFN layout (Sec. 3.2, Improvement 1) ---------------------
+//
+// T = pad->max_tp is the finest TP degree of the model's TP set.  Every FFN tensor is cut in
+// T partitions (gate/up by stored rows, down by stored columns, Eq. (1)); a rank at TP=t
+// stores its T/t partitions one after the other, each tensor-partition starting on a
+// multiple of page_bytes with zeros in the gap (U' = [U1,0,U2,0,..], D' likewise):
+//   layer = [qkv_r | o_r | zeros to a page][gate_p | 0][up_p | 0][down_p | 0] for p = r*T/t ..
+// with down_p stored as its own row-major [hidden][ffn/T] matrix.
+
+struct PadGeom {
+  int64_t attn, attn_padded;  // elements of the dense attention part, rounded up to a page
+  int64_t part, part_padded;  // elements of one tensor-partition (gate, up and down alike)
+  int64_t stride;             // elements from one partition to the next (3 padded tensors)
+  int64_t layer;              // elements per layer
+};
+
+int64_t round_up(int64_t x, int64_t g) { return (x + g - 1) / g * g; }
+
+PadGeom pad_geom(const ao_model* m, const ao_pad* pad, int tp) {
+  PadGeom g;
+  const int64_t page = pad->page_bytes / m->elem_bytes;
+  const ShardGeom d = geom(m, tp);
+  g.attn = d.off_gate_up;
+  g.attn_padded = round_up(g.attn, page);
+  g.part = (int64_t)m->ffn_dim / pad->max_tp * m->hidden;
+  g.part_padded = round_up(g.part, page);
+  g.stride = 3 * g.part_padded;
+  g.layer = g.attn_padded + (int64_t)(pad->max_tp / tp) * g.stride;
+  return g;
+}
+
+struct Loc { int64_t rank, off; };  // owning rank, element offset inside that rank's layer
+
+// Where element (row, col) of unsharded tensor `t` (0..6 = q,k,v,o,gate,up,down) lives at TP=tp.
+Loc locate(const ao_model* m, const ao_pad* pad, bool padded, int tp, int t, int64_t row,
+           int64_t col) {
+  const int64_t H = m->hidden, d = m->head_dim, I = m->ffn_dim;
+  const int64_t Nq = (int64_t)m->n_q_heads * d, Nkv = (int64_t)m->n_kv_heads * d;
+  const ShardGeom g = geom(m, tp);
+  const bool cut_rows = (t != 3 && t != 6);
+  const int64_t axis[7] = {Nq, Nkv, Nkv, Nq, I, I, I};
+  const int64_t per = axis[t] / tp;
+  const int64_t a = cut_rows ? row : col;     // index along the partitioned axis
+  Loc L;
+  L.rank = a / per;
+  const int64_t la = a % per;                 // the same index inside the owner's share
+  if (t <= 3 || !padded) {
+    switch (t) {
+      case 0: L.off = g.off_qkv + la * H + col; break;
+      case 1: L.off = g.off_qkv + g.q_rows * H + la * H + col; break;
+      case 2: L.off = g.off_qkv + (g.q_rows + g.kv_rows) * H + la * H + col; break;
+      case 3: L.off = g.off_o + row * g.o_cols + la; break;
+      case 4: L.off = g.off_gate_up + la * H + col; break;
+      case 5: L.off = g.off_gate_up + g.ffn_rows * H + la * H + col; break;
+      default: L.off = g.off_down + row * g.down_cols + la; break;
+    }
+    return L;
+  }
+  const PadGeom pg = pad_geom(m, pad, tp);
+  const int64_t w = I / pad->max_tp;          // rows (gate/up) or columns (down) per partition
+  const int64_t base = pg.attn_padded + (la / w) * pg.stride;
+  const int64_t in = la % w;
+  if (t == 4) L.off = base + in * H + col;
+  else if (t == 5) L.off = base + pg.part_padded + in * H + col;
+  else L.off = base + 2 * pg.part_padded + row * w + in;
+  return L;
+}
+
+bool pad_ok(const ao_model* m, const ao_pad* pad, int tp) {
+  return pad && pad->max_tp >= 1 && pad->page_bytes >= m->elem_bytes &&
+         pad->page_bytes % m->elem_bytes == 0 && m->ffn_dim % pad->max_tp == 0 &&
+         pad->max_tp % tp == 0;
+}
+
+template <typename E>
+int reshard_weights_padded_t(const ao_model* m, const ao_pad* pad, int k, int kp, int rp,
+                             const void* const* src_v, void* dst_v) {
+  const bool sp = pad->src_padded != 0, dp = pad->dst_padded != 0;
+  const int64_t src_layer = sp ? pad_geom(m, pad, k).layer : geom(m, k).layer_elems;
+  const int64_t dst_layer = dp ? pad_geom(m, pad, kp).layer : geom(m, kp).layer_elems;
+  const int64_t H = m->hidden, d = m->head_dim, I = m->ffn_dim;
+  const int64_t Nq = (int64_t)m->n_q_heads * d, Nkv = (int64_t)m->n_kv_heads * d;
+  const int64_t rows[7] = {Nq, Nkv, Nkv, H, I, I, H}, cols[7] = {H, H, H, Nq, H, H, I};
+  E* dst = static_cast<E*>(dst_v);
+  if (dp)  // the gaps hold zeros
+    for (int64_t i = 0; i < dst_layer * m->n_layers; ++i) dst[i] = 0;
+  for (int64_t l = 0; l < m->n_layers; ++l)
+    for (int t = 0; t < 7; ++t) {
+      const bool cut_rows = (t != 3 && t != 6);
+      const int64_t per = (cut_rows ? rows[t] : cols[t]) / kp;
+      const int64_t r0 = cut_rows ? rp * per : 0, r1 = cut_rows ? r0 + per : rows[t];
+      const int64_t c0 = cut_rows ? 0 : rp * per, c1 = cut_rows ? cols[t] : c0 + per;
+      for (int64_t r = r0; r < r1; ++r)
+        for (int64_t c = c0; c < c1; ++c) {
+          const Loc to = locate(m, pad, dp, kp, t, r, c);
+          const Loc from = locate(m, pad, sp, k, t, r, c);
+          const E* src = static_cast<const E*>(src_v[from.rank]);
+          if (!src) return AO_ERR_ARG;
+          dst[l * dst_layer + to.off] = src[l * src_layer + from.off];
+        }
+    }
+  return AO_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -323,6 +427,32 @@ int ao_merge_kv_inplace(const ao_kv* c, int src_tp, int m, int dst_rank, void* l
     default:
       return merge_kv_inplace_t<uint32_t>(c, src_tp, m, dst_rank, local_pool, remote_pools,
                                           src_tables, seq_lens, dst_table, remote_blocks_out);
+  }
+}
+
+int64_t ao_padded_shard_elems(const ao_model* m, const ao_pad* pad, int tp) {
+  if (!model_ok(m) || !tp_ok(m, tp) || !pad_ok(m, pad, tp)) return -1;
+  return pad_geom(m, pad, tp).layer * m->n_layers;
+}
+
+int ao_padded_geometry(const ao_model* m, const ao_pad* pad, int tp, int64_t out[6]) {
+  if (!model_ok(m) || !tp_ok(m, tp) || !pad_ok(m, pad, tp) || !out) return AO_ERR_ARG;
+  const PadGeom g = pad_geom(m, pad, tp);
+  out[0] = g.attn; out[1] = g.attn_padded; out[2] = g.part; out[3] = g.part_padded;
+  out[4] = g.stride; out[5] = g.layer;
+  return AO_OK;
+}
+
+int ao_reshard_weights_padded(const ao_model* m, const ao_pad* pad, int src_tp, int dst_tp,
+                              int dst_rank, const void* const* src_shards, void* dst) {
+  if (!model_ok(m) || src_tp > 64 || !tp_ok(m, src_tp) || !tp_ok(m, dst_tp) || dst_rank < 0 ||
+      dst_rank >= dst_tp || !src_shards || !dst || !pad_ok(m, pad, src_tp) ||
+      !pad_ok(m, pad, dst_tp))
+    return AO_ERR_ARG;
+  switch (m->elem_bytes) {
+    case 1: return reshard_weights_padded_t<uint8_t>(m, pad, src_tp, dst_tp, dst_rank, src_shards, dst);
+    case 2: return reshard_weights_padded_t<uint16_t>(m, pad, src_tp, dst_tp, dst_rank, src_shards, dst);
+    default: return reshard_weights_padded_t<uint32_t>(m, pad, src_tp, dst_tp, dst_rank, src_shards, dst);
   }
 }
 

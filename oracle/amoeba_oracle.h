@@ -120,6 +120,31 @@ int ao_merge_kv_inplace(const ao_kv* c, int src_tp, int m, int dst_rank, void* l
                         const int32_t* const* seq_lens, int32_t* dst_table,
                         int64_t* remote_blocks_out);
 
+/* Padded, partition-major FFN layout (Sec. 3.2, Improvement 1: padding at every potential
+ * TP boundary so that each partition starts on an allocation granule and a split only has
+ * to release pages).  max_tp = finest TP degree T; every FFN tensor is cut in T partitions;
+ * a rank at TP=t stores, per layer,
+ *   [qkv_r | o_r | zeros up to a page] then for each of its T/t partitions p:
+ *   [gate_p | zeros][up_p | zeros][down_p | zeros],   each tensor-partition page-aligned,
+ * gate_p/up_p = rows p*ffn/T.. of Wg/Wu ([ffn/T][hidden]), down_p = columns p*ffn/T.. of Wd
+ * stored as a row-major [hidden][ffn/T] matrix.  src_padded / dst_padded say which side of
+ * a reshard uses this layout (the other side is the dense shard). */
+typedef struct {
+  int32_t max_tp;
+  int32_t src_padded, dst_padded;
+  int64_t page_bytes;
+} ao_pad;
+
+/* Elements of one rank's padded shard at TP=tp (all layers); -1 if unsupported. */
+int64_t ao_padded_shard_elems(const ao_model* m, const ao_pad* pad, int tp);
+/* out = {attention elems, attention elems padded, tensor-partition elems, padded,
+ *        partition stride, layer elems} at TP=tp. */
+int ao_padded_geometry(const ao_model* m, const ao_pad* pad, int tp, int64_t out[6]);
+/* Like ao_reshard_weights with either side in the padded layout; gaps of a padded
+ * destination are zero-filled. */
+int ao_reshard_weights_padded(const ao_model* m, const ao_pad* pad, int src_tp, int dst_tp,
+                              int dst_rank, const void* const* src_shards, void* dst);
+
 #ifdef __cplusplus
 }
 #endif
