@@ -55,6 +55,22 @@ extern "C" {
 
 enum { AMOEBA_KV_HEAD_MAJOR = 0, AMOEBA_KV_TOKEN_MAJOR = 1 };
 
+/*
+ * AMOEBA_W_FFN_PADDED: the layout of Sec. 3.2, Improvement 1 ("parallelism-aware padding").
+ * Every FFN tensor is cut in T = pad_max_tp partitions (gate/up by stored rows, down by
+ * stored columns) and padding is added at every potential TP boundary so that each
+ * partition starts on a multiple of pad_page_bytes.  A rank at TP = t stores, per layer,
+ *     [qkv_r | o_r | zeros up to a page]
+ *     then for each of its T/t partitions p = r*T/t ..:  [gate_p | 0][up_p | 0][down_p | 0]
+ * gate_p / up_p = rows p*ffn/T .. of Wg / Wu ([ffn/T][hidden]); down_p = columns p*ffn/T ..
+ * of Wd as a row-major [hidden][ffn/T] matrix; every tensor-partition is page aligned and
+ * its gap holds zeros, so the FFN computed on the padded operands equals the FFN (Eq. (2)).
+ * A scale-up (t | t') then keeps a contiguous page range of each layer and releases the
+ * rest without copying (amoeba_plan_ffn_view); building the layout from a dense shard and
+ * gathering partitions on scale-down are amoeba_reshard_weights() calls on such a plan.
+ */
+enum { AMOEBA_W_DENSE = 0, AMOEBA_W_FFN_PADDED = 1 };
+
 enum {
   AMOEBA_OK = 0,
   AMOEBA_ERR_INVALID_ARG = 1, /* NULL plan / pointer, misaligned or aliased buffers      */
@@ -96,6 +112,13 @@ typedef struct {
   int32_t kv_layers;       /* layers held by each KV pool passed to amoeba_reshard_kv     */
   int32_t num_seqs, max_blocks_per_seq; /* block tables are [num_seqs][max_blocks_per_seq] */
   int64_t src_pool_blocks, dst_pool_blocks; /* blocks per layer in each pool              */
+  /* Weight shard layout of either side: AMOEBA_W_DENSE (0, the packing described above) or
+   * AMOEBA_W_FFN_PADDED, the padded partition-major FFN layout (see below).  With both 0
+   * the three pad_* fields are ignored. */
+  int32_t w_layout_src, w_layout_dst;
+  int32_t pad_max_tp;      /* T: finest TP degree of the model's TP set; src_tp, dst_tp | T */
+  int32_t pad_reserved;    /* 0 */
+  int64_t pad_page_bytes;  /* allocation granule the partitions are aligned to (2 MiB)    */
 } amoeba_model_shape;
 
 typedef struct amoeba_plan_s amoeba_plan_t;
@@ -216,12 +239,23 @@ uint32_t amoeba_plan_kv_rank_mask(const amoeba_plan_t* plan);
  * pointer may be NULL.  Returns AMOEBA_OK or AMOEBA_ERR_INVALID_ARG. */
 int amoeba_plan_tensor_info(const amoeba_plan_t* plan, int side, int tensor, int64_t* elem_off,
                             int64_t* rows, int64_t* cols, int64_t* layer_elems);
+/* Geometry of the padded layout of one side (bytes): out = {attention part, attention part
+ * padded, one tensor-partition, one tensor-partition padded, partition stride, layer}.
+ * AMOEBA_ERR_INVALID_ARG if that side is dense. */
+int amoeba_plan_padded_info(const amoeba_plan_t* plan, int side, int64_t out[6]);
+/* Zero-copy scale-up (Sec. 3.2: "directly release unused pages").  If both sides are padded
+ * and src_tp divides dst_tp, the target's FFN partitions are one page-aligned byte range of
+ * every layer of source rank out[0]: out = {source rank, byte offset of the range inside a
+ * source layer, bytes of the range, source layer bytes}.  Returns 1 if such a view exists,
+ * else 0.  (The attention part is re-sliced by head and is not a view.) */
+int amoeba_plan_ffn_view(const amoeba_plan_t* plan, int64_t out[4]);
 /* Strides, in elements, of (head, K/V, token, d) inside one block, and the block
  * size: what an attention kernel needs to read either layout unchanged
  * (Sec. 3.1, kv_stride_order()).  out[0..3] = strides, out[4] = block elements. */
 int amoeba_plan_kv_stride_order(const amoeba_plan_t* plan, int side, int64_t out[5]);
 /* Weight copy segments of one layer (for inspection and host-side tests).
- * out = {src_rank, src_byte_off, src_pitch, dst_byte_off, dst_pitch, rows, run_bytes}. */
+ * out = {src_rank, src_byte_off, src_pitch, dst_byte_off, dst_pitch, rows, run_bytes};
+ * src_rank = -1 marks a zero fill (a gap of a padded destination). */
 int amoeba_plan_num_segments(const amoeba_plan_t* plan);
 int amoeba_plan_segment(const amoeba_plan_t* plan, int index, int64_t out[7]);
 

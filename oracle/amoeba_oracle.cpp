@@ -286,20 +286,36 @@ PadGeom pad_geom(const ao_model* m, const ao_pad* pad, int tp) {
 
 struct Loc { int64_t rank, off; };  // owning rank, element offset inside that rank's layer
 
-// Where element (row, col) of unsharded tensor `t` (0..6 = q,k,v,o,gate,up,down) lives at TP=tp.
-Loc locate(const ao_model* m, const ao_pad* pad, bool padded, int tp, int t, int64_t row,
-           int64_t col) {
+// One side of a reshard: its TP degree, whether it uses the padded layout, its geometry.
+struct Side {
+  bool padded;
+  int tp;
+  ShardGeom g;
+  PadGeom pg;
+};
+
+Side make_side(const ao_model* m, const ao_pad* pad, bool padded, int tp) {
+  Side s;
+  s.padded = padded;
+  s.tp = tp;
+  s.g = geom(m, tp);
+  s.pg = pad_geom(m, pad, tp);
+  return s;
+}
+
+// Where element (row, col) of unsharded tensor `t` (0..6 = q,k,v,o,gate,up,down) lives on a side.
+Loc locate(const ao_model* m, const ao_pad* pad, const Side& sd, int t, int64_t row, int64_t col) {
   const int64_t H = m->hidden, d = m->head_dim, I = m->ffn_dim;
   const int64_t Nq = (int64_t)m->n_q_heads * d, Nkv = (int64_t)m->n_kv_heads * d;
-  const ShardGeom g = geom(m, tp);
+  const ShardGeom& g = sd.g;
   const bool cut_rows = (t != 3 && t != 6);
   const int64_t axis[7] = {Nq, Nkv, Nkv, Nq, I, I, I};
-  const int64_t per = axis[t] / tp;
+  const int64_t per = axis[t] / sd.tp;
   const int64_t a = cut_rows ? row : col;     // index along the partitioned axis
   Loc L;
   L.rank = a / per;
   const int64_t la = a % per;                 // the same index inside the owner's share
-  if (t <= 3 || !padded) {
+  if (t <= 3 || !sd.padded) {
     switch (t) {
       case 0: L.off = g.off_qkv + la * H + col; break;
       case 1: L.off = g.off_qkv + g.q_rows * H + la * H + col; break;
@@ -311,7 +327,7 @@ Loc locate(const ao_model* m, const ao_pad* pad, bool padded, int tp, int t, int
     }
     return L;
   }
-  const PadGeom pg = pad_geom(m, pad, tp);
+  const PadGeom& pg = sd.pg;
   const int64_t w = I / pad->max_tp;          // rows (gate/up) or columns (down) per partition
   const int64_t base = pg.attn_padded + (la / w) * pg.stride;
   const int64_t in = la % w;
@@ -331,8 +347,9 @@ template <typename E>
 int reshard_weights_padded_t(const ao_model* m, const ao_pad* pad, int k, int kp, int rp,
                              const void* const* src_v, void* dst_v) {
   const bool sp = pad->src_padded != 0, dp = pad->dst_padded != 0;
-  const int64_t src_layer = sp ? pad_geom(m, pad, k).layer : geom(m, k).layer_elems;
-  const int64_t dst_layer = dp ? pad_geom(m, pad, kp).layer : geom(m, kp).layer_elems;
+  const Side src_side = make_side(m, pad, sp, k), dst_side = make_side(m, pad, dp, kp);
+  const int64_t src_layer = sp ? src_side.pg.layer : src_side.g.layer_elems;
+  const int64_t dst_layer = dp ? dst_side.pg.layer : dst_side.g.layer_elems;
   const int64_t H = m->hidden, d = m->head_dim, I = m->ffn_dim;
   const int64_t Nq = (int64_t)m->n_q_heads * d, Nkv = (int64_t)m->n_kv_heads * d;
   const int64_t rows[7] = {Nq, Nkv, Nkv, H, I, I, H}, cols[7] = {H, H, H, Nq, H, H, I};
@@ -347,8 +364,8 @@ int reshard_weights_padded_t(const ao_model* m, const ao_pad* pad, int k, int kp
       const int64_t c0 = cut_rows ? 0 : rp * per, c1 = cut_rows ? cols[t] : c0 + per;
       for (int64_t r = r0; r < r1; ++r)
         for (int64_t c = c0; c < c1; ++c) {
-          const Loc to = locate(m, pad, dp, kp, t, r, c);
-          const Loc from = locate(m, pad, sp, k, t, r, c);
+          const Loc to = locate(m, pad, dst_side, t, r, c);
+          const Loc from = locate(m, pad, src_side, t, r, c);
           const E* src = static_cast<const E*>(src_v[from.rank]);
           if (!src) return AO_ERR_ARG;
           dst[l * dst_layer + to.off] = src[l * src_layer + from.off];

@@ -16,6 +16,9 @@ LIB_PATH = os.path.join(_HERE, "libamoeba.so")
 KV_HEAD_MAJOR = 0
 KV_TOKEN_MAJOR = 1
 
+W_DENSE = 0
+W_FFN_PADDED = 1
+
 OK, ERR_INVALID_ARG, ERR_HIP, ERR_OVERFLOW, ERR_BLOCK_ID = 0, 1, 2, 3, 4
 
 T_Q, T_K, T_V, T_O, T_GATE, T_UP, T_DOWN = range(7)
@@ -33,6 +36,7 @@ EXPORTS = [
     "amoeba_plan_kv_stride_order", "amoeba_plan_num_segments", "amoeba_plan_segment",
     "amoeba_plan_tune", "amoeba_copy_baseline", "amoeba_last_error",
     "amoeba_merge_kv_inplace", "amoeba_merge_kv_status", "amoeba_plan_merge_factor",
+    "amoeba_plan_padded_info", "amoeba_plan_ffn_view",
 ]
 
 
@@ -41,7 +45,10 @@ class _Shape(ctypes.Structure):
                 ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn_dim",
                  "elem_bytes", "kv_block_tokens", "kv_layout_src", "kv_layout_dst", "kv_layers",
                  "num_seqs", "max_blocks_per_seq")] + \
-               [("src_pool_blocks", ctypes.c_int64), ("dst_pool_blocks", ctypes.c_int64)]
+               [("src_pool_blocks", ctypes.c_int64), ("dst_pool_blocks", ctypes.c_int64),
+                ("w_layout_src", ctypes.c_int32), ("w_layout_dst", ctypes.c_int32),
+                ("pad_max_tp", ctypes.c_int32), ("pad_reserved", ctypes.c_int32),
+                ("pad_page_bytes", ctypes.c_int64)]
 
 
 @dataclass
@@ -62,6 +69,11 @@ class ModelShape:
     max_blocks_per_seq: int = 0
     src_pool_blocks: int = 0
     dst_pool_blocks: int = 0
+    w_layout_src: int = 0
+    w_layout_dst: int = 0
+    pad_max_tp: int = 0
+    pad_reserved: int = 0
+    pad_page_bytes: int = 0
 
     def _c(self) -> _Shape:
         return _Shape(*[getattr(self, f.name) for f in fields(self)])
@@ -119,6 +131,10 @@ def lib() -> ctypes.CDLL:
     L.amoeba_merge_kv_status.argtypes = [vp, vp, ctypes.POINTER(i64)]
     L.amoeba_plan_merge_factor.restype = i32
     L.amoeba_plan_merge_factor.argtypes = [vp]
+    L.amoeba_plan_padded_info.restype = i32
+    L.amoeba_plan_padded_info.argtypes = [vp, i32, ctypes.POINTER(i64)]
+    L.amoeba_plan_ffn_view.restype = i32
+    L.amoeba_plan_ffn_view.argtypes = [vp, ctypes.POINTER(i64)]
     L.amoeba_last_error.restype = ctypes.c_char_p
     L.amoeba_last_error.argtypes = []
     _lib = L
@@ -298,3 +314,21 @@ def amoeba_merge_kv_status(plan: Plan, stream=None):
     total = ctypes.c_int64(0)
     rc = lib().amoeba_merge_kv_status(plan.handle, _stream_handle(stream), ctypes.byref(total))
     return rc, int(total.value)
+
+
+def amoeba_plan_padded_info(plan: Plan, side: int):
+    """(attn, attn_padded, part, part_padded, stride, layer) in bytes for a padded side."""
+    out = (ctypes.c_int64 * 6)()
+    rc = lib().amoeba_plan_padded_info(plan.handle, side, out)
+    if rc != OK:
+        raise AmoebaError(rc, amoeba_last_error())
+    return tuple(int(x) for x in out)
+
+
+def amoeba_plan_ffn_view(plan: Plan):
+    """None, or (source rank, byte offset in a source layer, bytes, source layer bytes) when
+    the target's FFN partitions are a zero-copy range of a source rank's padded buffer."""
+    out = (ctypes.c_int64 * 4)()
+    if not lib().amoeba_plan_ffn_view(plan.handle, out):
+        return None
+    return tuple(int(x) for x in out)

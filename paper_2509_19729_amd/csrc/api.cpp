@@ -187,8 +187,7 @@ int amoeba_plan_merge_factor(const amoeba_plan_t* plan) { return plan ? plan->me
 
 size_t amoeba_plan_shard_bytes(const amoeba_plan_t* plan, int side) {
   if (!plan) return 0;
-  const amoeba::ShardLayout& L = side ? plan->dst_layout : plan->src_layout;
-  return size_t(L.layer_elems) * size_t(plan->shape.elem_bytes) * size_t(plan->shape.n_layers);
+  return size_t(side ? plan->dst_layer_bytes : plan->src_layer_bytes) * size_t(plan->shape.n_layers);
 }
 
 size_t amoeba_plan_kv_block_bytes(const amoeba_plan_t* plan, int side) {
@@ -216,6 +215,29 @@ int amoeba_plan_tensor_info(const amoeba_plan_t* plan, int side, int tensor, int
   if (cols) *cols = L.cols[tensor];
   if (layer_elems) *layer_elems = L.layer_elems;
   return AMOEBA_OK;
+}
+
+int amoeba_plan_padded_info(const amoeba_plan_t* plan, int side, int64_t out[6]) {
+  if (!plan || !out || (side != 0 && side != 1) || !(side ? plan->dst_padded : plan->src_padded)) {
+    set_error("amoeba_plan_padded_info: bad plan, side or out, or that side is dense");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  const amoeba::PaddedGeom& g = side ? plan->pad_dst : plan->pad_src;
+  out[0] = g.attn; out[1] = g.attn_padded; out[2] = g.part; out[3] = g.part_padded;
+  out[4] = g.stride; out[5] = g.layer;
+  return AMOEBA_OK;
+}
+
+int amoeba_plan_ffn_view(const amoeba_plan_t* plan, int64_t out[4]) {
+  if (!plan || !out || !plan->src_padded || !plan->dst_padded || plan->kp % plan->k) return 0;
+  const int64_t T = plan->shape.pad_max_tp;
+  const int64_t host = int64_t(plan->rp) * plan->k / plan->kp;  // source rank holding the range
+  const int64_t first = int64_t(plan->rp) * (T / plan->kp) - host * (T / plan->k);
+  out[0] = host;
+  out[1] = plan->pad_src.attn_padded + first * plan->pad_src.stride;
+  out[2] = (T / plan->kp) * plan->pad_src.stride;
+  out[3] = plan->pad_src.layer;
+  return 1;
 }
 
 int amoeba_plan_kv_stride_order(const amoeba_plan_t* plan, int side, int64_t out[5]) {

@@ -65,6 +65,17 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
       return fail(err, "TP degree must divide n_q_heads, n_kv_heads and ffn_dim");
   }
   if (rp < 0 || rp >= kp) return fail(err, "dst_rank outside [0, dst_tp)");
+  for (int lay : {s.w_layout_src, s.w_layout_dst})
+    if (lay != AMOEBA_W_DENSE && lay != AMOEBA_W_FFN_PADDED)
+      return fail(err, "unknown weight layout");
+  const bool any_padded = s.w_layout_src == AMOEBA_W_FFN_PADDED || s.w_layout_dst == AMOEBA_W_FFN_PADDED;
+  if (any_padded) {
+    if (s.pad_max_tp < 1 || s.pad_max_tp > AMOEBA_MAX_TP || s.ffn_dim % s.pad_max_tp ||
+        s.pad_max_tp % k || s.pad_max_tp % kp)
+      return fail(err, "pad_max_tp must be in [1, 16], divide ffn_dim and be a multiple of both TP degrees");
+    if (s.pad_page_bytes < s.elem_bytes || s.pad_page_bytes % s.elem_bytes)
+      return fail(err, "pad_page_bytes must be a positive multiple of elem_bytes");
+  }
 
   p->shape = s;
   p->k = k;
@@ -77,12 +88,35 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
 
   const int64_t e = s.elem_bytes;
   const int64_t d = s.head_dim;
+  p->src_padded = s.w_layout_src == AMOEBA_W_FFN_PADDED;
+  p->dst_padded = s.w_layout_dst == AMOEBA_W_FFN_PADDED;
+  p->src_layer_bytes = p->src_layout.layer_elems * e;
+  p->dst_layer_bytes = p->dst_layout.layer_elems * e;
+  if (any_padded) {
+    const int64_t G = s.pad_page_bytes, T = s.pad_max_tp;
+    auto pages = [G](int64_t bytes) { return (bytes + G - 1) / G * G; };
+    auto padded_geom = [&](const ShardLayout& L, int tp) {
+      PaddedGeom g;
+      g.attn = L.off[AMOEBA_T_GATE] * e;  // q, k, v, o come first and stay dense
+      g.attn_padded = pages(g.attn);
+      g.part = int64_t(s.ffn_dim) / T * s.hidden * e;
+      g.part_padded = pages(g.part);
+      g.stride = 3 * g.part_padded;
+      g.layer = g.attn_padded + (T / tp) * g.stride;
+      return g;
+    };
+    p->pad_src = padded_geom(p->src_layout, k);
+    p->pad_dst = padded_geom(p->dst_layout, kp);
+    if (p->src_padded) p->src_layer_bytes = p->pad_src.layer;
+    if (p->dst_padded) p->dst_layer_bytes = p->pad_dst.layer;
+  }
   // extent of the partitioned axis of each tensor in the unsharded model
   const int64_t axis[AMOEBA_T_COUNT] = {int64_t(s.n_q_heads) * d, int64_t(s.n_kv_heads) * d,
                                         int64_t(s.n_kv_heads) * d, int64_t(s.n_q_heads) * d,
                                         s.ffn_dim,                 s.ffn_dim,
                                         s.ffn_dim};
   for (int t = 0; t < AMOEBA_T_COUNT; ++t) {
+    if (any_padded && t >= AMOEBA_T_GATE) break;  // FFN tensors: per partition, below
     const bool cut_on_rows = (t != AMOEBA_T_O && t != AMOEBA_T_DOWN);
     const int64_t N = axis[t], per_src = N / k, per_dst = N / kp;
     const int64_t want_lo = rp * per_dst, want_hi = want_lo + per_dst;
@@ -113,6 +147,69 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
       }
       p->segments.push_back(g);
       p->weight_rank_mask |= 1u << r;
+    }
+  }
+
+  if (any_padded) {
+    // Sec. 3.2, Improvement 1.  Walk the finest partitions the target rank owns; each one
+    // lives on exactly one source rank.  On a padded side a tensor-partition is one
+    // contiguous, page-aligned range; on a dense side gate/up partitions are row ranges of
+    // the fused tensor and a down partition is a column range (strided).
+    const int64_t T = s.pad_max_tp, w = int64_t(s.ffn_dim) / T, H = s.hidden;
+    const int64_t per_src = T / k, per_dst = T / kp;
+    auto zero_fill = [&](int64_t off, int64_t bytes) {
+      if (bytes <= 0) return;
+      Segment z;
+      z.src_rank = -1;
+      z.src_off = 0;
+      z.dst_off = off;
+      z.rows = 1;
+      z.run = z.src_pitch = z.dst_pitch = bytes;
+      p->segments.push_back(z);
+    };
+    if (p->dst_padded) zero_fill(p->pad_dst.attn, p->pad_dst.attn_padded - p->pad_dst.attn);
+    for (int64_t q = 0; q < per_dst; ++q) {
+      const int64_t part = rp * per_dst + q;  // global partition index
+      const int64_t r = part / per_src, qs = part - r * per_src;
+      for (int t = AMOEBA_T_GATE; t <= AMOEBA_T_DOWN; ++t) {
+        const int slot = t - AMOEBA_T_GATE;
+        const bool is_down = t == AMOEBA_T_DOWN;
+        Segment g;
+        g.src_rank = int32_t(r);
+        // source side
+        if (p->src_padded) {
+          g.src_off = p->pad_src.attn_padded + qs * p->pad_src.stride + slot * p->pad_src.part_padded;
+          g.src_pitch = w * e;
+        } else if (!is_down) {
+          g.src_off = (p->src_layout.off[t] + qs * w * H) * e;
+          g.src_pitch = H * e;
+        } else {
+          g.src_off = (p->src_layout.off[t] + qs * w) * e;
+          g.src_pitch = p->src_layout.cols[t] * e;
+        }
+        // target side
+        if (p->dst_padded) {
+          g.dst_off = p->pad_dst.attn_padded + q * p->pad_dst.stride + slot * p->pad_dst.part_padded;
+          g.dst_pitch = w * e;
+        } else if (!is_down) {
+          g.dst_off = (p->dst_layout.off[t] + q * w * H) * e;
+          g.dst_pitch = H * e;
+        } else {
+          g.dst_off = (p->dst_layout.off[t] + q * w) * e;
+          g.dst_pitch = p->dst_layout.cols[t] * e;
+        }
+        if (!is_down || (g.src_pitch == w * e && g.dst_pitch == w * e)) {
+          g.rows = 1;  // contiguous on both sides
+          g.run = w * H * e;
+          g.src_pitch = g.dst_pitch = g.run;
+        } else {
+          g.rows = H;
+          g.run = w * e;
+        }
+        p->segments.push_back(g);
+        p->weight_rank_mask |= 1u << r;
+        if (p->dst_padded) zero_fill(g.dst_off + p->pad_dst.part, p->pad_dst.part_padded - p->pad_dst.part);
+      }
     }
   }
 

@@ -30,6 +30,14 @@ struct Segment {
   int64_t rows, run;
 };
 
+// Padded partition-major FFN layout of one side, in bytes.
+struct PaddedGeom {
+  int64_t attn, attn_padded;  // dense attention part, rounded up to a page
+  int64_t part, part_padded;  // one tensor-partition (gate, up and down are equal in size)
+  int64_t stride;             // from one partition to the next: 3 padded tensor-partitions
+  int64_t layer;
+};
+
 struct Tuning {
   int w_grid = 0, w_unroll = 0, w_threads = 0, kv_grid = 0, kv_unroll = 0, kv_threads = 0,
       nontemporal = 0, kv_staged = 0, kv_blocks_hint = 0;
@@ -41,7 +49,10 @@ struct amoeba_plan_s {
   amoeba_model_shape shape;
   int k, kp, rp;
   amoeba::ShardLayout src_layout, dst_layout;
-  std::vector<amoeba::Segment> segments;  // one layer's worth, target order
+  std::vector<amoeba::Segment> segments;  // one layer's worth, target order; src_rank -1 = zeros
+  bool src_padded, dst_padded;
+  amoeba::PaddedGeom pad_src, pad_dst;     // valid where the side is padded
+  int64_t src_layer_bytes, dst_layer_bytes;
   uint32_t weight_rank_mask, kv_rank_mask;
   // KV geometry
   int64_t heads_src, heads_dst;            // KV heads per rank on either side

@@ -79,7 +79,7 @@ __global__ void __launch_bounds__(THREADS) reshard_weights_kernel(const WArgs a)
       const uint32_t col = n - row * s.row_vecs.d;
       const uint64_t soff = uint64_t(row) * s.src_pitch + uint64_t(col) * VEC;
       doff[u] = uint64_t(row) * s.dst_pitch + uint64_t(col) * VEC;
-      if (live[u]) val[u] = ld<NT, V>(src + soff);
+      if (live[u]) val[u] = s.src ? ld<NT, V>(src + soff) : V(0);
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
@@ -130,15 +130,15 @@ void dispatch(int vec, int threads, int unroll, bool nt, dim3 grid, hipStream_t 
 
 int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards, void* dst,
                            hipStream_t stream, std::string* err) {
-  const int64_t e = p->shape.elem_bytes;
-  const int64_t src_layer = p->src_layout.layer_elems * e, dst_layer = p->dst_layout.layer_elems * e;
+  const int64_t src_layer = p->src_layer_bytes, dst_layer = p->dst_layer_bytes;
   const uint64_t src_bytes = uint64_t(src_layer) * p->shape.n_layers,
                  dst_bytes = uint64_t(dst_layer) * p->shape.n_layers;
 
   // widest access every address of this call is aligned to
   uint64_t bits = uint64_t(src_layer) | uint64_t(dst_layer) | reinterpret_cast<uint64_t>(dst);
   for (const Segment& g : p->segments) {
-    bits |= uint64_t(g.src_off) | uint64_t(g.dst_off) | uint64_t(g.run);
+    bits |= uint64_t(g.dst_off) | uint64_t(g.run);
+    if (g.src_rank >= 0) bits |= uint64_t(g.src_off);
     if (g.rows > 1) bits |= uint64_t(g.src_pitch) | uint64_t(g.dst_pitch);
   }
   const uint64_t d0 = reinterpret_cast<uint64_t>(dst);
@@ -179,7 +179,8 @@ int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards
         return AMOEBA_ERR_INVALID_ARG;
       }
       WSeg& s = a.seg[i];
-      s.src = static_cast<const char*>(src_shards[g.src_rank]) + g.src_off;
+      s.src = g.src_rank < 0 ? nullptr  // a gap of a padded target: zeros
+                             : static_cast<const char*>(src_shards[g.src_rank]) + g.src_off;
       s.dst_off = g.dst_off;
       s.src_pitch = strided ? uint32_t(g.src_pitch) : 0;  // a single row never uses its pitch
       s.dst_pitch = strided ? uint32_t(g.dst_pitch) : 0;
