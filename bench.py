@@ -36,11 +36,13 @@ def parse():
                     help="KV layers resident per call (0 = all that fit the workload definition)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", default="", help="knob=value,... (AMOEBA_TUNE_* names, lower case)")
-    ap.add_argument("--mode", default="reshard", choices=["reshard", "merge-inplace", "merge-naive"],
+    ap.add_argument("--mode", default="reshard", choices=["reshard", "merge-inplace", "merge-naive", "weights-padded"],
                     help="reshard: the TP k -> k' hot path (default, the headline metric); "
                          "merge-inplace: m x TP1 instances -> TP m, KV cache only, in place; "
                          "merge-naive: the same scenario the paper's base way (token-first "
-                         "blocks, every block of every instance moved into a fresh pool)")
+                         "blocks, every block of every instance moved into a fresh pool); "
+                         "weights-padded: TP1 <-> TP4 weight transformation with the padded "
+                         "FFN layout against the dense layout (the paper's partial swap)")
     ap.add_argument("--instances", type=int, default=4, help="m for --mode merge-inplace")
     ap.add_argument("--no-hint", action="store_true",
                     help="merge-inplace: do not tell the library how many blocks are in use")
@@ -69,6 +71,8 @@ def main():
         return merge_inplace(args)
     if args.mode == "merge-naive":
         return merge_naive(args)
+    if args.mode == "weights-padded":
+        return weights_padded(args)
     w = wl.WORKLOADS[args.workload]
     lay = {"hm": ab.KV_HEAD_MAJOR, "tm": ab.KV_TOKEN_MAJOR}
     lay_s, lay_d = (lay[x] for x in args.layout.split("-"))
@@ -202,6 +206,90 @@ def main():
         out["cpu_baseline"] = cpu_baseline(w, lens, table, src_pool_blocks, dst_pool_blocks,
                                            lay_s, lay_d)
     plan.close()
+    print(json.dumps(out), flush=True)
+
+
+def weights_padded(args):
+    """Weight transformation TP1 <-> TP4 of the workload's model, dense layout against the
+    padded partition-major FFN layout (2 MiB pages, T = 4).  Dense scale-up is the paper's
+    "partial swap" (the kept partition is copied to the front); padded scale-up keeps a page
+    range and copies only the attention part; scale-down gathers the other partitions."""
+    import torch
+
+    from paper_2509_19729_amd import binding as ab
+    from paper_2509_19729_amd import workloads as wl
+
+    w = wl.WORKLOADS[args.workload]
+    T, page = 4, 2 << 20
+
+    def shape(sp, dp):
+        return ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim,
+                             w.ffn_dim, elem_bytes=2, w_layout_src=sp, w_layout_dst=dp,
+                             pad_max_tp=T, pad_page_bytes=page)
+
+    def timed(plan, src, dst):
+        for _ in range(args.warmup):
+            ab.amoeba_reshard_weights(plan, src, dst)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            ab.amoeba_reshard_weights(plan, src, dst)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    def buf(nbytes):
+        return torch.empty(nbytes // 2, dtype=torch.bfloat16, device="cuda").normal_(0.0, 0.02)
+
+    res = {}
+    # scale-up 1 -> 4, rank 1: dense (copy the whole shard) vs padded (attention part only)
+    p_dense = ab.amoeba_plan(shape(0, 0), 1, 4, 1)
+    src = [buf(ab.amoeba_plan_shard_bytes(p_dense, 0))]
+    dst = buf(ab.amoeba_plan_shard_bytes(p_dense, 1))
+    ms = timed(p_dense, src, dst)
+    res["scale_up_dense_partial_swap"] = {"ms": round(ms, 4),
+                                          "bytes_copied": ab.amoeba_plan_shard_bytes(p_dense, 1)}
+    del src, dst
+    torch.cuda.empty_cache()
+    p_pad = ab.amoeba_plan(shape(1, 1), 1, 4, 1)
+    rank, off, nbytes, src_layer = ab.amoeba_plan_ffn_view(p_pad)
+    attn = ab.amoeba_plan_padded_info(p_pad, 1)[0]
+    # the FFN partitions stay where they are; only q/k/v/o are re-sliced (into a fresh buffer)
+    ab.amoeba_plan_tune(p_pad, ab.TUNE_W_PART, 1)
+    a_src = [buf(ab.amoeba_plan_shard_bytes(p_pad, 0))]
+    a_dst = buf(ab.amoeba_plan_shard_bytes(p_pad, 1))
+    ms_attn = timed(p_pad, a_src, a_dst)
+    res["scale_up_padded"] = {"ms": round(ms_attn, 4), "bytes_copied": attn * w.n_layers,
+                              "ffn_bytes_kept_in_place": nbytes * w.n_layers,
+                              "ffn_bytes_released": (src_layer - off - nbytes + off -
+                                                     ab.amoeba_plan_padded_info(p_pad, 0)[1])
+                              * w.n_layers}
+    del a_src, a_dst
+    torch.cuda.empty_cache()
+    # scale-down 4 -> 1: dense gather vs padded gather (both move the whole model)
+    for name, sp in (("scale_down_dense", 0), ("scale_down_padded", 1)):
+        plan = ab.amoeba_plan(shape(sp, sp), 4, 1, 0)
+        src = [buf(ab.amoeba_plan_shard_bytes(plan, 0)) for _ in range(4)]
+        dst = buf(ab.amoeba_plan_shard_bytes(plan, 1))
+        ms = timed(plan, src, dst)
+        nb = ab.amoeba_plan_shard_bytes(plan, 1)
+        res[name] = {"ms": round(ms, 4), "bytes_copied": nb,
+                     "gbps_read_plus_write": round(2 * nb / (ms * 1e-3) / 1e9, 1)}
+        if sp:
+            info = ab.amoeba_plan_padded_info(plan, 1)
+            res["padding_overhead"] = round((info[3] - info[2]) / info[2], 5)
+        del src, dst
+        torch.cuda.empty_cache()
+        plan.close()
+    up = res["scale_up_dense_partial_swap"]
+    out = {"metric": "weight transformation TP1 <-> TP4, dense vs padded FFN layout", "unit": "ms",
+           "value": res["scale_up_padded"]["ms"], "higher_is_better": False, "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "data": "synthetic", "dtype": "u16",
+           "config": {"workload": f"{w.name}: {w.n_layers} layers, hidden {w.hidden}, ffn "
+                                  f"{w.ffn_dim}, T = {T}, 2 MiB pages, target rank 1 / 0"},
+           "results": res,
+           "scale_up_time_saved": round(1 - res["scale_up_padded"]["ms"] / up["ms"], 4)}
     print(json.dumps(out), flush=True)
 
 

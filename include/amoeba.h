@@ -95,12 +95,15 @@ enum {
   AMOEBA_TUNE_KV_THREADS = 5,  /* lanes per workgroup: 64 or 256                             */
   AMOEBA_TUNE_NONTEMPORAL = 6, /* 1: streaming (nt) loads/stores, 2: plain                   */
   AMOEBA_TUNE_KV_STAGED = 7,   /* 1: LDS-staged layout-converting regroup, 2: direct         */
-  AMOEBA_TUNE_KV_BLOCKS_HINT = 8 /* upper bound on the blocks the next KV calls will move (the
+  AMOEBA_TUNE_KV_BLOCKS_HINT = 8, /* upper bound on the blocks the next KV calls will move (the
                                   host scheduler knows it; the library only sees device-side
                                   lengths).  Sizes the grid: without it the grid covers the
                                   pool's capacity and idle workgroups cost dispatch time when
                                   the pool is far from full.  A hint that is too small is
                                   still correct (workgroups stride), only slower.            */
+  AMOEBA_TUNE_W_PART = 9       /* amoeba_reshard_weights moves 0: everything, 1: only q/k/v/o
+                                  (for a padded scale-up whose FFN part is a zero-copy view,
+                                  see amoeba_plan_ffn_view), 2: only the FFN tensors        */
 };
 
 /* Caller-owned POD; amoeba_plan() copies it. */

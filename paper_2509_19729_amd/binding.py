@@ -24,7 +24,7 @@ OK, ERR_INVALID_ARG, ERR_HIP, ERR_OVERFLOW, ERR_BLOCK_ID = 0, 1, 2, 3, 4
 T_Q, T_K, T_V, T_O, T_GATE, T_UP, T_DOWN = range(7)
 
 TUNE_W_GRID, TUNE_W_UNROLL, TUNE_W_THREADS, TUNE_KV_GRID, TUNE_KV_UNROLL, TUNE_KV_THREADS, \
-    TUNE_NONTEMPORAL, TUNE_KV_STAGED, TUNE_KV_BLOCKS_HINT = range(9)
+    TUNE_NONTEMPORAL, TUNE_KV_STAGED, TUNE_KV_BLOCKS_HINT, TUNE_W_PART = range(10)
 
 MAX_TP = 16
 

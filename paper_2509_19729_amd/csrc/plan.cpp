@@ -125,6 +125,7 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
       if (lo >= hi) continue;
       Segment g;
       g.src_rank = r;
+      g.part = t >= AMOEBA_T_GATE;
       if (cut_on_rows) {
         const int64_t width = p->src_layout.cols[t];  // == hidden on both sides
         g.src_off = (p->src_layout.off[t] + (lo - r * per_src) * width) * e;
@@ -157,17 +158,18 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
     // the fused tensor and a down partition is a column range (strided).
     const int64_t T = s.pad_max_tp, w = int64_t(s.ffn_dim) / T, H = s.hidden;
     const int64_t per_src = T / k, per_dst = T / kp;
-    auto zero_fill = [&](int64_t off, int64_t bytes) {
+    auto zero_fill = [&](int64_t off, int64_t bytes, int part) {
       if (bytes <= 0) return;
       Segment z;
       z.src_rank = -1;
+      z.part = part;
       z.src_off = 0;
       z.dst_off = off;
       z.rows = 1;
       z.run = z.src_pitch = z.dst_pitch = bytes;
       p->segments.push_back(z);
     };
-    if (p->dst_padded) zero_fill(p->pad_dst.attn, p->pad_dst.attn_padded - p->pad_dst.attn);
+    if (p->dst_padded) zero_fill(p->pad_dst.attn, p->pad_dst.attn_padded - p->pad_dst.attn, 0);
     for (int64_t q = 0; q < per_dst; ++q) {
       const int64_t part = rp * per_dst + q;  // global partition index
       const int64_t r = part / per_src, qs = part - r * per_src;
@@ -176,6 +178,7 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
         const bool is_down = t == AMOEBA_T_DOWN;
         Segment g;
         g.src_rank = int32_t(r);
+        g.part = 1;
         // source side
         if (p->src_padded) {
           g.src_off = p->pad_src.attn_padded + qs * p->pad_src.stride + slot * p->pad_src.part_padded;
@@ -208,7 +211,8 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
         }
         p->segments.push_back(g);
         p->weight_rank_mask |= 1u << r;
-        if (p->dst_padded) zero_fill(g.dst_off + p->pad_dst.part, p->pad_dst.part_padded - p->pad_dst.part);
+        if (p->dst_padded)
+          zero_fill(g.dst_off + p->pad_dst.part, p->pad_dst.part_padded - p->pad_dst.part, 1);
       }
     }
   }

@@ -24,7 +24,8 @@ struct ShardLayout {
 // one layer: `rows` runs of `run` bytes, `*_pitch` bytes apart.  A contiguous copy
 // has rows == 1.
 struct Segment {
-  int32_t src_rank;
+  int32_t src_rank;  // -1: fill with zeros
+  int32_t part;      // 0: attention tensors (q, k, v, o and their gap), 1: FFN tensors
   int64_t src_off, src_pitch;
   int64_t dst_off, dst_pitch;
   int64_t rows, run;
@@ -40,7 +41,7 @@ struct PaddedGeom {
 
 struct Tuning {
   int w_grid = 0, w_unroll = 0, w_threads = 0, kv_grid = 0, kv_unroll = 0, kv_threads = 0,
-      nontemporal = 0, kv_staged = 0, kv_blocks_hint = 0;
+      nontemporal = 0, kv_staged = 0, kv_blocks_hint = 0, w_part = 0;
 };
 
 }  // namespace amoeba

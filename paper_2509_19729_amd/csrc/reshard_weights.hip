@@ -20,6 +20,7 @@
 // multiply-high division by the row length.
 #include <algorithm>
 #include <string>
+#include <vector>
 
 #include "device_common.h"
 #include "launch.h"
@@ -160,7 +161,11 @@ int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards
   const bool nt = p->tune.nontemporal != 2;
   const uint64_t tile_vecs = uint64_t(threads) * unroll;
 
-  const size_t n = p->segments.size();
+  // AMOEBA_TUNE_W_PART: move only the attention tensors (1) or only the FFN tensors (2)
+  std::vector<Segment> chosen;
+  for (const Segment& g : p->segments)
+    if (p->tune.w_part == 0 || p->tune.w_part == g.part + 1) chosen.push_back(g);
+  const size_t n = chosen.size();
   for (size_t first = 0; first < n; first += kMaxSegs) {
     WArgs a;
     a.dst = static_cast<char*>(dst);
@@ -169,7 +174,7 @@ int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards
     a.n_seg = uint32_t(std::min<size_t>(kMaxSegs, n - first));
     uint64_t tiles = 0;
     for (uint32_t i = 0; i < a.n_seg; ++i) {
-      const Segment& g = p->segments[first + i];
+      const Segment& g = chosen[first + i];
       const uint64_t row_vecs = uint64_t(g.run) / vec, total = row_vecs * uint64_t(g.rows);
       const bool strided = g.rows > 1;
       if (total >= (uint64_t(1) << 32) - 65536 ||

@@ -102,3 +102,40 @@ def test_padded_unaligned_partitions_with_2mib_pages():
     pad = oracle.Pad(4, page, True, True)
     src = sources(m, pad, 4, seed=4)
     check(m, pad, 4, 2, 1, src)
+
+
+def test_moving_only_the_attention_part_or_only_the_ffn_part():
+    """AMOEBA_TUNE_W_PART splits one reshard in two disjoint halves: the attention tensors and
+    the FFN tensors.  Each half leaves the other half's bytes alone; together they give the
+    oracle's shard.  (A padded scale-up uses the attention half only: its FFN is a view.)"""
+    m = oracle.Model(n_layers=2, hidden=64, n_q_heads=8, n_kv_heads=4, head_dim=8, ffn_dim=96)
+    for pad in (oracle.Pad(4, 256, True, True), oracle.Pad(4, 256, False, False)):
+        k, kp, rp = 1, 4, 2
+        src = sources(m, pad, k, seed=6)
+        if pad.dst_padded:
+            st, want = oracle.reshard_weights_padded(m, pad, k, kp, rp, src)
+        else:
+            st, want = oracle.reshard_weights(m, k, kp, rp, src)
+        assert st == oracle.OK
+        plan = ab.amoeba_plan(shape(m, pad), k, kp, rp)
+        n = ab.amoeba_plan_shard_bytes(plan, 1)
+        dev = [to_dev(a) for a in src]
+        halves = []
+        for part in (1, 2):
+            ab.amoeba_plan_tune(plan, ab.TUNE_W_PART, part)
+            out = torch.full((n,), 0x5C, dtype=torch.uint8, device="cuda")
+            ab.amoeba_reshard_weights(plan, dev, out)
+            torch.cuda.synchronize()
+            halves.append(out.cpu().numpy())
+        a, f = halves
+        w = want.view(np.uint8)
+        touched_a, touched_f = a != 0x5C, f != 0x5C
+        assert not (touched_a & touched_f).any()
+        assert (a[touched_a] == w[touched_a]).all() and (f[touched_f] == w[touched_f]).all()
+        # bytes neither half changed must be bytes whose value happens to equal the sentinel
+        assert (w[~(touched_a | touched_f)] == 0x5C).all()
+        layer = n // m.n_layers
+        attn_bytes = (8 * 8 // kp + 2 * 4 * 8 // kp) * 64 * 2 + 64 * (8 * 8 // kp) * 2
+        first_ffn = np.nonzero(touched_f)[0].min()
+        assert np.nonzero(touched_a)[0].max() % layer < first_ffn + layer and first_ffn >= attn_bytes
+        plan.close()
