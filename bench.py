@@ -35,6 +35,10 @@ def parse():
     ap.add_argument("--kv-layers", type=int, default=0,
                     help="KV layers resident per call (0 = all that fit the workload definition)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--head-dim", type=int, default=0,
+                    help="override the workload's head_dim (with --kv-heads: other head geometries "
+                         "on the same sequence table, e.g. 64-byte head vectors)")
+    ap.add_argument("--kv-heads", type=int, default=0, help="override n_kv_heads = n_q_heads")
     ap.add_argument("--tune", default="", help="knob=value,... (AMOEBA_TUNE_* names, lower case)")
     ap.add_argument("--mode", default="reshard", choices=["reshard", "merge-inplace", "merge-naive", "weights-padded"],
                     help="reshard: the TP k -> k' hot path (default, the headline metric); "
@@ -74,6 +78,10 @@ def main():
     if args.mode == "weights-padded":
         return weights_padded(args)
     w = wl.WORKLOADS[args.workload]
+    if args.head_dim or args.kv_heads:
+        heads = args.kv_heads or w.n_kv_heads
+        w = w.scaled(head_dim=args.head_dim or w.head_dim, n_kv_heads=heads, n_q_heads=heads,
+                     name=f"{w.name}-d{args.head_dim or w.head_dim}-h{heads}")
     lay = {"hm": ab.KV_HEAD_MAJOR, "tm": ab.KV_TOKEN_MAJOR}
     lay_s, lay_d = (lay[x] for x in args.layout.split("-"))
 
@@ -83,7 +91,7 @@ def main():
     dst_pool_blocks = total_blocks + 64
     kv_layers = args.kv_layers or w.n_layers
     if w.name == "llama13b" and not args.kv_layers:
-        kv_layers = 16  # the full 40-layer cache (src + dst) exceeds 288 GB; see the design doc
+        kv_layers = 16  # the full 40-layer cache (src + dst, about 494 GB) exceeds the 288 GB of HBM
     shape = ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim,
                           elem_bytes=w.elem_bytes, kv_block_tokens=w.block_tokens,
                           kv_layout_src=lay_s, kv_layout_dst=lay_d, kv_layers=kv_layers,
