@@ -119,3 +119,34 @@ def test_kv_full_size_matches_oracle_on_sampled_layers_and_index_select_on_all(f
             ref = src[r].view(L, src_pool, bs)[layer].index_select(0, order)
             got = dst3[layer, :total, half * bs:(half + 1) * bs]
             assert torch.equal(got, ref), f"layer {layer} rank {r}"
+
+
+def test_weights_70b_gqa_full_depth_sampled_layers_match_oracle():
+    """TP8 -> TP4 rank 2 of the 70B-shaped GQA model at all 80 layers: a 31.9 GiB target shard
+    from two 15.9 GiB source shards, so every offset past 2^32 and 2^34 bytes is exercised."""
+    w = wl.WORKLOADS["gqa70b"]
+    shape = ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim)
+    plan = ab.amoeba_plan(shape, w.src_tp, w.dst_tp, w.dst_rank)
+    sb, db = ab.amoeba_plan_shard_bytes(plan, 0), ab.amoeba_plan_shard_bytes(plan, 1)
+    mask = ab.amoeba_plan_src_rank_mask(plan)
+    assert {r for r in range(w.src_tp) if mask >> r & 1} == {4, 5}
+    src = [random_device_bits(sb // 2, seed=60 + r) if mask >> r & 1 else None
+           for r in range(w.src_tp)]
+    dst = torch.full((db // 2,), 0x5A5A, dtype=torch.int16, device="cuda")
+    ab.amoeba_reshard_weights(plan, src, dst)
+    torch.cuda.synchronize()
+    one = oracle.Model(1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim)
+    ls, ld = sb // 2 // w.n_layers, db // 2 // w.n_layers
+    for layer in (0, 41, w.n_layers - 1):
+        host_src = [None if t is None else t[layer * ls:(layer + 1) * ls].cpu().numpy().view(np.uint16)
+                    for t in src]
+        st, want = oracle.reshard_weights(one, w.src_tp, w.dst_tp, w.dst_rank, host_src)
+        assert st == oracle.OK
+        got = dst[layer * ld:(layer + 1) * ld].cpu().numpy().view(np.uint16)
+        np.testing.assert_array_equal(got, want, err_msg=f"layer {layer}")
+    d = dst.view(w.n_layers, ld).to(torch.int64).sum(dim=1)
+    s = sum(t.view(w.n_layers, ls).to(torch.int64).sum(dim=1) for t in src if t is not None)
+    assert torch.equal(d, s)
+    plan.close()
+    del src, dst
+    torch.cuda.empty_cache()
