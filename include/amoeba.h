@@ -267,13 +267,13 @@ int amoeba_plan_segment(const amoeba_plan_t* plan, int index, int64_t out[7]);
 int amoeba_plan_tune(amoeba_plan_t* plan, int knob, int value);
 
 /* Measurement aid, not part of the reshard: a plain device-to-device streaming copy
- * with the same access shape as the reshard kernels (16 B per lane, `unroll` loads in
- * flight per lane: 1, 2, 4 or 8; `grid` workgroups, 0 = one per tile; nontemporal as in
- * AMOEBA_TUNE_NONTEMPORAL).  Gives the copy rate this GPU reaches and a transfer of
+ * with the same access shape as the reshard kernels (16 B per lane, `threads` lanes per
+ * workgroup: 64 or 256; `unroll` loads in flight per lane: 1, 2, 4 or 8; `grid` workgroups,
+ * 0 = one per tile; nontemporal as in AMOEBA_TUNE_NONTEMPORAL).  Gives the copy rate this GPU reaches and a transfer of
  * known size to calibrate HBM traffic counters.  dst, src: DEVICE pointers, 16-byte
  * aligned, non-overlapping; bytes a multiple of 16. */
-int amoeba_copy_baseline(void* dst, const void* src, size_t bytes, int unroll, int grid,
-                         int nontemporal, void* stream);
+int amoeba_copy_baseline(void* dst, const void* src, size_t bytes, int threads, int unroll,
+                         int grid, int nontemporal, void* stream);
 
 /* Text of the calling thread's last error ("" if none). */
 const char* amoeba_last_error(void);

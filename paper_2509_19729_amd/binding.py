@@ -123,7 +123,7 @@ def lib() -> ctypes.CDLL:
     L.amoeba_plan_tune.restype = i32
     L.amoeba_plan_tune.argtypes = [vp, i32, i32]
     L.amoeba_copy_baseline.restype = i32
-    L.amoeba_copy_baseline.argtypes = [vp, vp, ctypes.c_size_t, i32, i32, i32, vp]
+    L.amoeba_copy_baseline.argtypes = [vp, vp, ctypes.c_size_t, i32, i32, i32, i32, vp]
     L.amoeba_merge_kv_inplace.restype = i32
     L.amoeba_merge_kv_inplace.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                           ctypes.POINTER(vp), vp, vp]
@@ -286,10 +286,10 @@ def amoeba_plan_tune(plan: Plan, knob: int, value: int) -> None:
         raise AmoebaError(rc, amoeba_last_error())
 
 
-def amoeba_copy_baseline(dst, src, nbytes: int, unroll: int = 4, grid: int = 0,
+def amoeba_copy_baseline(dst, src, nbytes: int, threads: int = 64, unroll: int = 1, grid: int = 0,
                          nontemporal: int = 1, stream=None) -> None:
-    rc = lib().amoeba_copy_baseline(_ptr(dst), _ptr(src), nbytes, unroll, grid, nontemporal,
-                                    _stream_handle(stream))
+    rc = lib().amoeba_copy_baseline(_ptr(dst), _ptr(src), nbytes, threads, unroll, grid,
+                                    nontemporal, _stream_handle(stream))
     if rc != OK:
         raise AmoebaError(rc, amoeba_last_error())
 

@@ -272,11 +272,11 @@ int amoeba_plan_segment(const amoeba_plan_t* plan, int index, int64_t out[7]) {
   return AMOEBA_OK;
 }
 
-int amoeba_copy_baseline(void* dst, const void* src, size_t bytes, int unroll, int grid,
-                         int nontemporal, void* stream) {
+int amoeba_copy_baseline(void* dst, const void* src, size_t bytes, int threads, int unroll,
+                         int grid, int nontemporal, void* stream) {
   if (!dst || !src) { set_error("amoeba_copy_baseline: NULL pointer"); return AMOEBA_ERR_INVALID_ARG; }
   std::string err;
-  const int rc = amoeba::launch_copy_baseline(dst, src, bytes, unroll, grid, nontemporal != 2,
+  const int rc = amoeba::launch_copy_baseline(dst, src, bytes, threads, unroll, grid, nontemporal != 2,
                                               static_cast<hipStream_t>(stream), &err);
   if (rc != AMOEBA_OK) set_error("amoeba_copy_baseline: " + err);
   return rc;

@@ -31,7 +31,7 @@ int launch_merge_kv_inplace(const amoeba_plan_s* p, void* local_pool,
                             const int32_t* const* seq_lens, int32_t* dst_block_tables,
                             hipStream_t stream, std::string* err);
 
-int launch_copy_baseline(void* dst, const void* src, size_t bytes, int unroll, int grid, bool nt,
-                         hipStream_t stream, std::string* err);
+int launch_copy_baseline(void* dst, const void* src, size_t bytes, int threads, int unroll, int grid,
+                         bool nt, hipStream_t stream, std::string* err);
 
 }  // namespace amoeba
