@@ -266,6 +266,11 @@ int launch_merge_kv_inplace(const amoeba_plan_s* p, void* local_pool,
     *err = "the plan has no device workspace (it was created without a GPU)";
     return AMOEBA_ERR_HIP;
   }
+  int current_device = -1;
+  if (hipGetDevice(&current_device) != hipSuccess || current_device != p->device) {
+    *err = "the current device is not the one the plan's workspace was allocated on";
+    return AMOEBA_ERR_INVALID_ARG;
+  }
   const uint32_t m = uint32_t(p->merge_factor), g = uint32_t(p->rp) % m;
   const uint64_t S = uint64_t(s.num_seqs), W = uint64_t(s.max_blocks_per_seq);
   const uint64_t cells = uint64_t(m) * S * W;

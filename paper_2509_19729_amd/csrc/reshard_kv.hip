@@ -19,7 +19,8 @@
 //                    a tile is a run of 16-byte vectors contiguous in the
 //                    destination block.  The number of blocks in use is only
 //                    known on the device, so the grid covers the pool's capacity
-//                    (capped) and idle workgroups leave at once.  A lane turns its
+//                    (or the caller's bound on the blocks in use) and idle
+//                    workgroups leave at once.  A lane turns its
 //                    vector index into (head, K/V*token, d-offset) for the
 //                    destination layout with multiply-high divisions, maps the head
 //                    to (source rank, local head) and rebuilds the index for the
@@ -357,6 +358,11 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
   if (!p->workspace) {
     *err = "the plan has no device workspace (it was created without a GPU)";
     return AMOEBA_ERR_HIP;
+  }
+  int current_device = -1;
+  if (hipGetDevice(&current_device) != hipSuccess || current_device != p->device) {
+    *err = "the current device is not the one the plan's workspace was allocated on";
+    return AMOEBA_ERR_INVALID_ARG;
   }
   const uint64_t cells = uint64_t(s.num_seqs) * uint64_t(s.max_blocks_per_seq);
   if (cells >= (uint64_t(1) << 32) - kThreads) {
