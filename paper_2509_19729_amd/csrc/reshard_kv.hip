@@ -421,13 +421,57 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
     if (!hip_ok("kv table kernel launch failed", err)) return AMOEBA_ERR_HIP;
   }
   // 3. regroup
+  if (cells == 0 || s.dst_pool_blocks == 0) return AMOEBA_OK;
+  const uint32_t B = uint32_t(s.kv_block_tokens);
+  const uint32_t dv = uint32_t(head_vec_bytes / vec);  // vectors of one head vector
+  a.dst = static_cast<char*>(dst_blocks);
+  a.ws = p->workspace;
+  a.src_layer_stride = src_layer;
+  a.dst_layer_stride = dst_layer;
+  a.src_block_bytes = uint64_t(p->block_bytes_src);
+  a.dst_block_bytes = uint64_t(p->block_bytes_dst);
+  a.num_seqs = uint32_t(s.num_seqs);
+  a.head0 = uint32_t(p->rp * p->heads_dst);
+  a.rank_lo = a.head0 / uint32_t(p->heads_src);
+  a.rank_hi = (a.head0 + uint32_t(p->heads_dst) - 1) / uint32_t(p->heads_src);
+  a.n_src = a.rank_hi - a.rank_lo + 1;
+  a.src_lo = a.src[a.rank_lo];
+  a.src_hi = a.src[a.rank_hi];
+  a.heads_src = make_fastdiv(uint32_t(p->heads_src));
+  a.heads_dst = make_fastdiv(uint32_t(p->heads_dst));
+  a.dv = make_fastdiv(dv);
+  a.head_vecs = make_fastdiv(2u * B * dv);
+  const uint64_t block_vecs = uint64_t(p->block_bytes_dst) / vec;
+  a.block_vecs = uint32_t(block_vecs);
+
+  // Grid: one workgroup per tile of the pool's capacity (workgroups that stride over several
+  // tiles measured 8 % slower), or of the caller's bound on the blocks in use; capped at 2^27
+  // workgroups over all layers so that a huge, mostly empty pool does not pay for idle
+  // workgroups without limit.  Past the grid, workgroups stride.
+  auto grid_for = [&](uint64_t tiles_per_block, dim3* out) {
+    const uint64_t max_items = uint64_t(s.dst_pool_blocks) * tiles_per_block;  // per layer
+    if (block_vecs >= (uint64_t(1) << 32) - 65536 ||
+        max_items >= (uint64_t(1) << 32) - (1 << 24) || s.kv_layers > 65535)
+      return false;
+    uint64_t grid =
+        std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 27) / uint64_t(s.kv_layers));
+    if (p->tune.kv_grid > 0) grid = uint64_t(p->tune.kv_grid);
+    grid = std::min<uint64_t>(grid, max_items);
+    if (p->tune.kv_blocks_hint > 0)
+      grid = std::min<uint64_t>(
+          grid, std::max<uint64_t>(1, uint64_t(p->tune.kv_blocks_hint) * tiles_per_block));
+    *out = dim3(uint32_t(grid), uint32_t(s.kv_layers));
+    return true;
+  };
+  dim3 grid;
+
   // Converting between the layouts goes through LDS when one head vector is shorter than
   // a cache line (see kv_regroup_staged_kernel); with 256-byte head vectors the direct
   // gather already moves whole lines and measured the same or faster.
   const bool convert = s.kv_layout_src != s.kv_layout_dst;
-  const bool want_staged = p->tune.kv_staged == 1 || (p->tune.kv_staged == 0 && head_vec_bytes < 128);
+  const bool want_staged =
+      p->tune.kv_staged == 1 || (p->tune.kv_staged == 0 && head_vec_bytes < 128);
   if (convert && vec == 16 && want_staged && head_vec_bytes <= 4096) {
-    const uint32_t dv = uint32_t(head_vec_bytes / 16), B = uint32_t(s.kv_block_tokens);
     const uint32_t target = 4096u * uint32_t(unroll == 1 ? 2 : unroll);  // tile bytes aimed at
     uint32_t tt = std::max<uint32_t>(1, 1024u / uint32_t(head_vec_bytes));
     tt = std::min(tt, B);
@@ -444,44 +488,16 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
     g.fd_tile_heads = make_fastdiv(th);
     const uint64_t head_groups = (uint64_t(p->heads_dst) + th - 1) / th;
     const uint64_t tiles_per_block = head_groups * 2 * (B / tt);
-    const uint64_t max_items = uint64_t(s.dst_pool_blocks) * tiles_per_block;
-    if (max_items >= (uint64_t(1) << 32) - (1 << 24) || s.kv_layers > 65535) {
+    a.tiles_per_block = make_fastdiv(uint32_t(tiles_per_block));
+    if (!grid_for(tiles_per_block, &grid)) {
       *err = "KV pool too large for 32-bit work indexing";
       return AMOEBA_ERR_INVALID_ARG;
     }
-    if (max_items == 0 || cells == 0) return AMOEBA_OK;
-    a.dst = static_cast<char*>(dst_blocks);
-    a.ws = p->workspace;
-    a.src_layer_stride = src_layer;
-    a.dst_layer_stride = dst_layer;
-    a.src_block_bytes = uint64_t(p->block_bytes_src);
-    a.dst_block_bytes = uint64_t(p->block_bytes_dst);
-    a.num_seqs = uint32_t(s.num_seqs);
-    a.block_vecs = uint32_t(uint64_t(p->block_bytes_dst) / 16);
-    a.tiles_per_block = make_fastdiv(uint32_t(tiles_per_block));
-    a.head0 = uint32_t(p->rp * p->heads_dst);
-    a.rank_lo = a.head0 / uint32_t(p->heads_src);
-    a.rank_hi = (a.head0 + uint32_t(p->heads_dst) - 1) / uint32_t(p->heads_src);
-    a.n_src = a.rank_hi - a.rank_lo + 1;
-    a.src_lo = a.src[a.rank_lo];
-    a.src_hi = a.src[a.rank_hi];
-    a.heads_src = make_fastdiv(uint32_t(p->heads_src));
-    a.heads_dst = make_fastdiv(uint32_t(p->heads_dst));
-    a.dv = make_fastdiv(dv);
-    a.head_vecs = make_fastdiv(2u * B * dv);
-    uint64_t grid = std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 27) / uint64_t(s.kv_layers));
-    if (p->tune.kv_grid > 0) grid = uint64_t(p->tune.kv_grid);
-    grid = std::min<uint64_t>(grid, max_items);
-    if (p->tune.kv_blocks_hint > 0)
-      grid = std::min<uint64_t>(
-          grid, std::max<uint64_t>(1, uint64_t(p->tune.kv_blocks_hint) * tiles_per_block));
-    const dim3 gr(uint32_t(grid), uint32_t(s.kv_layers));
     const size_t lds = size_t(g.tile_vecs) * 16;
-    const bool src_hm = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR;
-#define AMOEBA_STAGED(SL, DL, NTV)                                                             \
-  hipLaunchKernelGGL((kv_regroup_staged_kernel<SL, DL, NTV>), gr, dim3(kThreads), lds, stream, \
-                     a, g, a.ws)
-    if (src_hm) {
+#define AMOEBA_STAGED(SL, DL, NTV)                                                        \
+  hipLaunchKernelGGL((kv_regroup_staged_kernel<SL, DL, NTV>), grid, dim3(kThreads), lds,  \
+                     stream, a, g, a.ws)
+    if (s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR) {
       if (nt) AMOEBA_STAGED(AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR, true);
       else AMOEBA_STAGED(AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR, false);
     } else {
@@ -492,57 +508,23 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
     if (!hip_ok("kv staged regroup kernel launch failed", err)) return AMOEBA_ERR_HIP;
     return AMOEBA_OK;
   }
-  const uint64_t block_vecs = uint64_t(p->block_bytes_dst) / vec;
+
   const uint64_t tile_vecs = uint64_t(threads) * unroll;
   const uint64_t tiles_per_block = (block_vecs + tile_vecs - 1) / tile_vecs;
-  const uint64_t max_items = uint64_t(s.dst_pool_blocks) * tiles_per_block;  // per layer
-  if (block_vecs >= (uint64_t(1) << 32) - 65536 || max_items >= (uint64_t(1) << 32) - (1 << 24) ||
-      s.kv_layers > 65535) {
+  a.tiles_per_block = make_fastdiv(uint32_t(tiles_per_block));
+  if (!grid_for(tiles_per_block, &grid)) {
     *err = "KV pool too large for 32-bit work indexing";
     return AMOEBA_ERR_INVALID_ARG;
   }
-  if (max_items == 0 || cells == 0) return AMOEBA_OK;
-  a.dst = static_cast<char*>(dst_blocks);
-  a.ws = p->workspace;
-  a.src_layer_stride = src_layer;
-  a.dst_layer_stride = dst_layer;
-  a.src_block_bytes = uint64_t(p->block_bytes_src);
-  a.dst_block_bytes = uint64_t(p->block_bytes_dst);
-  a.num_seqs = uint32_t(s.num_seqs);
-  a.block_vecs = uint32_t(block_vecs);
-  a.tiles_per_block = make_fastdiv(uint32_t(tiles_per_block));
-  a.head0 = uint32_t(p->rp * p->heads_dst);
-  a.rank_lo = a.head0 / uint32_t(p->heads_src);
-  a.rank_hi = (a.head0 + uint32_t(p->heads_dst) - 1) / uint32_t(p->heads_src);
-  a.n_src = a.rank_hi - a.rank_lo + 1;
-  a.src_lo = a.src[a.rank_lo];
-  a.src_hi = a.src[a.rank_hi];
-  a.heads_src = make_fastdiv(uint32_t(p->heads_src));
-  a.heads_dst = make_fastdiv(uint32_t(p->heads_dst));
-  const uint32_t dv = uint32_t(head_vec_bytes / vec);
-  a.dv = make_fastdiv(dv);
-  a.head_vecs = make_fastdiv(uint32_t(2u * uint32_t(s.kv_block_tokens) * dv));
-
-  // One workgroup per tile of the pool's capacity: workgroups that stride over several
-  // tiles measured 8 % slower.  The grid is capped at 2^27 workgroups over all layers so
-  // that a huge, mostly empty pool does not pay for idle workgroups without bound; past
-  // the cap workgroups stride.
-  uint64_t grid = std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 27) / uint64_t(s.kv_layers));
-  if (p->tune.kv_grid > 0) grid = uint64_t(p->tune.kv_grid);
-  grid = std::min<uint64_t>(grid, max_items);
-  if (p->tune.kv_blocks_hint > 0)
-    grid = std::min<uint64_t>(
-        grid, std::max<uint64_t>(1, uint64_t(p->tune.kv_blocks_hint) * tiles_per_block));
-  const dim3 g(uint32_t(grid), uint32_t(s.kv_layers));
   const bool sh = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR, dh = s.kv_layout_dst == AMOEBA_KV_HEAD_MAJOR;
   if (sh && dh)
-    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, threads, unroll, nt, g, stream, a);
+    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, threads, unroll, nt, grid, stream, a);
   else if (sh && !dh)
-    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, threads, unroll, nt, g, stream, a);
+    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, threads, unroll, nt, grid, stream, a);
   else if (!sh && dh)
-    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, threads, unroll, nt, g, stream, a);
+    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, threads, unroll, nt, grid, stream, a);
   else
-    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, threads, unroll, nt, g, stream, a);
+    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, threads, unroll, nt, grid, stream, a);
   if (!hip_ok("kv regroup kernel launch failed", err)) return AMOEBA_ERR_HIP;
   return AMOEBA_OK;
 }
