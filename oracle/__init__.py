@@ -54,6 +54,23 @@ class _Pad(ctypes.Structure):
                 ("dst_padded", ctypes.c_int32), ("page_bytes", ctypes.c_int64)]
 
 
+class _Moe(ctypes.Structure):
+    _fields_ = [("n_experts", ctypes.c_int32), ("src_padded", ctypes.c_int32),
+                ("dst_padded", ctypes.c_int32), ("page_bytes", ctypes.c_int64)]
+
+
+@dataclass(frozen=True)
+class Moe:
+    """Expert-wise FFN layout (Sec. 3.2, EP discussion); Model.ffn_dim is one expert's size."""
+    n_experts: int
+    page_bytes: int = 0
+    src_padded: bool = False
+    dst_padded: bool = False
+
+    def _c(self):
+        return _Moe(self.n_experts, int(self.src_padded), int(self.dst_padded), self.page_bytes)
+
+
 @dataclass(frozen=True)
 class Pad:
     """Padded FFN layout parameters (Sec. 3.2, Improvement 1)."""
@@ -138,6 +155,16 @@ def lib():
         L.ao_reshard_weights_padded.argtypes = [ctypes.POINTER(_Model), ctypes.POINTER(_Pad),
                                                 ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                 ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p]
+        L.ao_moe_shard_elems.restype = ctypes.c_int64
+        L.ao_moe_shard_elems.argtypes = [ctypes.POINTER(_Model), ctypes.POINTER(_Moe),
+                                         ctypes.c_int, ctypes.c_int]
+        L.ao_moe_geometry.restype = ctypes.c_int
+        L.ao_moe_geometry.argtypes = [ctypes.POINTER(_Model), ctypes.POINTER(_Moe), ctypes.c_int,
+                                      ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]
+        L.ao_reshard_weights_moe.restype = ctypes.c_int
+        L.ao_reshard_weights_moe.argtypes = [ctypes.POINTER(_Model), ctypes.POINTER(_Moe),
+                                             ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                             ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -245,4 +272,29 @@ def reshard_weights_padded(m: Model, pad: Pad, src_tp: int, dst_tp: int, dst_ran
     ptrs, _keep = _ptr_array(src_shards, max(src_tp, 1), dt)
     st = lib().ao_reshard_weights_padded(ctypes.byref(m._c()), ctypes.byref(pad._c()), src_tp,
                                          dst_tp, dst_rank, ptrs, dst.ctypes.data)
+    return int(st), dst
+
+
+def moe_shard_elems(m: Model, x: Moe, padded: bool, tp: int) -> int:
+    return int(lib().ao_moe_shard_elems(ctypes.byref(m._c()), ctypes.byref(x._c()), int(padded), tp))
+
+
+def moe_geometry(m: Model, x: Moe, padded: bool, tp: int):
+    """(experts per rank, first expert offset, tensor, tensor stride, layer) in elements."""
+    out = (ctypes.c_int64 * 5)()
+    st = lib().ao_moe_geometry(ctypes.byref(m._c()), ctypes.byref(x._c()), int(padded), tp, out)
+    assert st == OK
+    return tuple(int(v) for v in out)
+
+
+def reshard_weights_moe(m: Model, x: Moe, src_tp: int, dst_tp: int, dst_rank: int, src_shards,
+                        dst=None):
+    """Mixture-of-experts reshard (attention by head, whole experts).  Returns (status, dst)."""
+    dt = elem_dtype(m.elem_bytes)
+    n = moe_shard_elems(m, x, x.dst_padded, dst_tp)
+    if dst is None:
+        dst = np.full(max(n, 0), 0xEE, dtype=dt)
+    ptrs, _keep = _ptr_array(src_shards, max(src_tp, 1), dt)
+    st = lib().ao_reshard_weights_moe(ctypes.byref(m._c()), ctypes.byref(x._c()), src_tp, dst_tp,
+                                      dst_rank, ptrs, dst.ctypes.data)
     return int(st), dst

@@ -374,6 +374,81 @@ int reshard_weights_padded_t(const ao_model* m, const ao_pad* pad, int k, int kp
   return AO_OK;
 }
 
+// ---- mixture of experts (Sec. 3.2, EP discussion; TPkEPk of Sec. 4.3) ---------------------
+// Attention tensors are cut by head as in the dense model; the FFN is stored expert by expert
+// and rank r at degree t owns experts [r*E/t, (r+1)*E/t) whole.
+
+bool moe_ok(const ao_model* m, const ao_moe* x, int tp) {
+  return x && x->n_experts > 0 && divides(tp, m->n_q_heads) && divides(tp, m->n_kv_heads) &&
+         divides(tp, x->n_experts) &&
+         (x->page_bytes == 0 || (x->page_bytes >= m->elem_bytes && x->page_bytes % m->elem_bytes == 0));
+}
+
+struct MoeGeom {
+  int64_t own;      // experts per rank
+  int64_t first;    // element offset of the first expert tensor in a layer
+  int64_t tensor;   // elements of one expert tensor
+  int64_t slot;     // elements from one expert tensor to the next
+  int64_t layer;
+};
+
+MoeGeom moe_geom(const ao_model* m, const ao_moe* x, bool padded, int tp) {
+  MoeGeom g;
+  const int64_t page = padded ? x->page_bytes / m->elem_bytes : 1;  // in elements
+  const int64_t attn = geom(m, tp).off_gate_up;                     // q, k, v, o of this rank
+  g.own = x->n_experts / tp;
+  g.first = (attn + page - 1) / page * page;
+  g.tensor = (int64_t)m->ffn_dim * m->hidden;
+  g.slot = (g.tensor + page - 1) / page * page;
+  g.layer = g.first + g.own * 3 * g.slot;
+  return g;
+}
+
+template <typename E>
+int reshard_weights_moe_t(const ao_model* m, const ao_moe* x, int k, int kp, int rp,
+                          const void* const* src_v, void* dst_v) {
+  const bool sp = x->src_padded && x->page_bytes, dp = x->dst_padded && x->page_bytes;
+  const ShardGeom as = geom(m, k), ad = geom(m, kp);  // attention offsets only
+  const MoeGeom gs = moe_geom(m, x, sp, k), gd = moe_geom(m, x, dp, kp);
+  const int64_t H = m->hidden, d = m->head_dim;
+  const int64_t Nq = (int64_t)m->n_q_heads * d, Nkv = (int64_t)m->n_kv_heads * d;
+  const E* src[64];
+  for (int s = 0; s < k; ++s) src[s] = static_cast<const E*>(src_v[s]);
+  E* dst = static_cast<E*>(dst_v);
+  // every source rank that owns a wanted head or expert must be present
+  for (int s = 0; s < k; ++s) {
+    bool needed = false;
+    const int64_t tot[3] = {m->n_q_heads, m->n_kv_heads, x->n_experts};
+    for (int a = 0; a < 3; ++a) {
+      const int64_t lo = rp * (tot[a] / kp), hi = lo + tot[a] / kp;
+      const int64_t slo = s * (tot[a] / k), shi = slo + tot[a] / k;
+      if (lo < shi && slo < hi) needed = true;
+    }
+    if (needed && !src[s]) return AO_ERR_ARG;
+  }
+  if (dp)
+    for (int64_t i = 0; i < gd.layer * m->n_layers; ++i) dst[i] = 0;
+  for (int64_t l = 0; l < m->n_layers; ++l) {
+    const int64_t sb = l * gs.layer, db = l * gd.layer;
+    gather_row_cut(src, dst, sb, db, as.off_qkv, ad.off_qkv, Nq, H, k, kp, rp);
+    gather_row_cut(src, dst, sb, db, as.off_qkv + as.q_rows * H, ad.off_qkv + ad.q_rows * H, Nkv,
+                   H, k, kp, rp);
+    gather_row_cut(src, dst, sb, db, as.off_qkv + (as.q_rows + as.kv_rows) * H,
+                   ad.off_qkv + (ad.q_rows + ad.kv_rows) * H, Nkv, H, k, kp, rp);
+    gather_col_cut(src, dst, sb, db, as.off_o, ad.off_o, H, Nq, k, kp, rp);
+    for (int64_t j = 0; j < gd.own; ++j) {       // j-th expert of the target rank
+      const int64_t ex = rp * gd.own + j;        // its index in the model
+      const int64_t s = ex / gs.own;             // source rank that owns it
+      const int64_t js = ex % gs.own;            // its position on that rank
+      for (int64_t w = 0; w < 3; ++w)            // gate, up, down
+        for (int64_t i = 0; i < gd.tensor; ++i)
+          dst[db + gd.first + (j * 3 + w) * gd.slot + i] =
+              src[s][sb + gs.first + (js * 3 + w) * gs.slot + i];
+    }
+  }
+  return AO_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -470,6 +545,30 @@ int ao_reshard_weights_padded(const ao_model* m, const ao_pad* pad, int src_tp, 
     case 1: return reshard_weights_padded_t<uint8_t>(m, pad, src_tp, dst_tp, dst_rank, src_shards, dst);
     case 2: return reshard_weights_padded_t<uint16_t>(m, pad, src_tp, dst_tp, dst_rank, src_shards, dst);
     default: return reshard_weights_padded_t<uint32_t>(m, pad, src_tp, dst_tp, dst_rank, src_shards, dst);
+  }
+}
+
+int64_t ao_moe_shard_elems(const ao_model* m, const ao_moe* x, int padded, int tp) {
+  if (!model_ok(m) || !moe_ok(m, x, tp)) return -1;
+  return moe_geom(m, x, padded && x->page_bytes, tp).layer * m->n_layers;
+}
+
+int ao_moe_geometry(const ao_model* m, const ao_moe* x, int padded, int tp, int64_t out[5]) {
+  if (!model_ok(m) || !moe_ok(m, x, tp) || !out) return AO_ERR_ARG;
+  const MoeGeom g = moe_geom(m, x, padded && x->page_bytes, tp);
+  out[0] = g.own; out[1] = g.first; out[2] = g.tensor; out[3] = g.slot; out[4] = g.layer;
+  return AO_OK;
+}
+
+int ao_reshard_weights_moe(const ao_model* m, const ao_moe* x, int src_tp, int dst_tp,
+                           int dst_rank, const void* const* src_shards, void* dst) {
+  if (!model_ok(m) || src_tp > 64 || !moe_ok(m, x, src_tp) || !moe_ok(m, x, dst_tp) ||
+      dst_rank < 0 || dst_rank >= dst_tp || !src_shards || !dst)
+    return AO_ERR_ARG;
+  switch (m->elem_bytes) {
+    case 1: return reshard_weights_moe_t<uint8_t>(m, x, src_tp, dst_tp, dst_rank, src_shards, dst);
+    case 2: return reshard_weights_moe_t<uint16_t>(m, x, src_tp, dst_tp, dst_rank, src_shards, dst);
+    default: return reshard_weights_moe_t<uint32_t>(m, x, src_tp, dst_tp, dst_rank, src_shards, dst);
   }
 }
 

@@ -145,6 +145,31 @@ int ao_padded_geometry(const ao_model* m, const ao_pad* pad, int tp, int64_t out
 int ao_reshard_weights_padded(const ao_model* m, const ao_pad* pad, int src_tp, int dst_tp,
                               int dst_rank, const void* const* src_shards, void* dst);
 
+/* Mixture-of-experts model (Sec. 3.2, "Supporting EP transformation": the FFN is stored in an
+ * expert-wise layout, so experts that leave a rank are released whole; Sec. 4.3 runs
+ * 4 x (TP1 EP1) -> TP4 EP4).  m->ffn_dim is ONE expert's intermediate size f; every expert e
+ * has Wg_e[f, hidden], Wu_e[f, hidden], Wd_e[hidden, f].  Attention tensors are cut by head
+ * as in the dense model; rank r at degree t owns experts [r*E/t, (r+1)*E/t) (the paper does
+ * not print the expert-to-rank rule; contiguous ranges, like its head rule).  Per layer a
+ * rank stores [qkv_r | o_r] and then, for each owned expert in order, [gate_e][up_e][down_e].
+ * On a padded side (page_bytes > 0 and the side's flag set) the attention part is rounded up
+ * to a page and every expert tensor starts on a page boundary, the gaps holding zeros. */
+typedef struct {
+  int32_t n_experts;
+  int32_t src_padded, dst_padded;
+  int64_t page_bytes; /* 0: no padding anywhere */
+} ao_moe;
+
+/* Elements of one rank's shard at degree tp, all layers; -1 if unsupported. */
+int64_t ao_moe_shard_elems(const ao_model* m, const ao_moe* x, int padded, int tp);
+/* out = {experts per rank, offset of the first expert tensor, expert tensor elems, stride
+ *        between expert tensors, layer elems}, in elements. */
+int ao_moe_geometry(const ao_model* m, const ao_moe* x, int padded, int tp, int64_t out[5]);
+/* dst <- rank dst_rank's shard at degree dst_tp (attention TP, experts EP), gathered from the
+ * src_tp shards; gaps of a padded destination are zero-filled. */
+int ao_reshard_weights_moe(const ao_model* m, const ao_moe* x, int src_tp, int dst_tp,
+                           int dst_rank, const void* const* src_shards, void* dst);
+
 #ifdef __cplusplus
 }
 #endif
