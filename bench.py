@@ -100,7 +100,8 @@ def main():
                           elem_bytes=w.elem_bytes, kv_block_tokens=w.block_tokens,
                           kv_layout_src=lay_s, kv_layout_dst=lay_d, kv_layers=kv_layers,
                           num_seqs=w.num_seqs, max_blocks_per_seq=table.shape[1],
-                          src_pool_blocks=src_pool_blocks, dst_pool_blocks=dst_pool_blocks)
+                          src_pool_blocks=src_pool_blocks, dst_pool_blocks=dst_pool_blocks,
+                          n_experts=w.n_experts)
     plan = ab.amoeba_plan(shape, w.src_tp, w.dst_tp, w.dst_rank)
     # the scheduler that owns the block tables knows how many blocks are in use; the library
     # only sees device-side lengths and would otherwise size its grid by the pool's capacity
@@ -243,7 +244,8 @@ def weights_padded(args):
     """Weight transformation TP1 <-> TP4 of the workload's model, dense layout against the
     padded partition-major FFN layout (2 MiB pages, T = 4).  Dense scale-up is the paper's
     "partial swap" (the kept partition is copied to the front); padded scale-up keeps a page
-    range and copies only the attention part; scale-down gathers the other partitions."""
+    range and copies only the attention part; scale-down gathers the other partitions.  For a
+    mixture-of-experts workload the partitions are whole experts (TP1 EP1 <-> TP4 EP4)."""
     import torch
 
     from paper_2509_19729_amd import binding as ab
@@ -255,7 +257,13 @@ def weights_padded(args):
     def shape(sp, dp):
         return ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim,
                              w.ffn_dim, elem_bytes=2, w_layout_src=sp, w_layout_dst=dp,
-                             pad_max_tp=T, pad_page_bytes=page)
+                             pad_max_tp=T, pad_page_bytes=page, n_experts=w.n_experts)
+
+    def ffn_start(plan, side):
+        """Bytes of a layer in front of the FFN part (attention tensors + their padding)."""
+        if w.n_experts:
+            return ab.amoeba_plan_expert_info(plan, side)[1]
+        return ab.amoeba_plan_padded_info(plan, side)[1]
 
     def timed(plan, src, dst):
         for _ in range(args.warmup):
@@ -284,7 +292,7 @@ def weights_padded(args):
     torch.cuda.empty_cache()
     p_pad = ab.amoeba_plan(shape(1, 1), 1, 4, 1)
     rank, off, nbytes, src_layer = ab.amoeba_plan_ffn_view(p_pad)
-    attn = ab.amoeba_plan_padded_info(p_pad, 1)[0]
+    attn = ffn_start(p_pad, 1)
     # the FFN partitions stay where they are; only q/k/v/o are re-sliced (into a fresh buffer)
     ab.amoeba_plan_tune(p_pad, ab.TUNE_W_PART, 1)
     a_src = [buf(ab.amoeba_plan_shard_bytes(p_pad, 0))]
@@ -292,8 +300,7 @@ def weights_padded(args):
     ms_attn = timed(p_pad, a_src, a_dst)
     res["scale_up_padded"] = {"ms": round(ms_attn, 4), "bytes_copied": attn * w.n_layers,
                               "ffn_bytes_kept_in_place": nbytes * w.n_layers,
-                              "ffn_bytes_released": (src_layer - off - nbytes + off -
-                                                     ab.amoeba_plan_padded_info(p_pad, 0)[1])
+                              "ffn_bytes_released": (src_layer - nbytes - ffn_start(p_pad, 0))
                               * w.n_layers}
     del a_src, a_dst
     torch.cuda.empty_cache()
@@ -306,7 +313,10 @@ def weights_padded(args):
         nb = ab.amoeba_plan_shard_bytes(plan, 1)
         res[name] = {"ms": round(ms, 4), "bytes_copied": nb,
                      "gbps_read_plus_write": round(2 * nb / (ms * 1e-3) / 1e9, 1)}
-        if sp:
+        if sp and w.n_experts:
+            _, _, tensor, slot = ab.amoeba_plan_expert_info(plan, 1)
+            res["padding_overhead"] = round((slot - 3 * tensor) / (3 * tensor), 5)
+        elif sp:
             info = ab.amoeba_plan_padded_info(plan, 1)
             res["padding_overhead"] = round((info[3] - info[2]) / info[2], 5)
         del src, dst
@@ -317,7 +327,8 @@ def weights_padded(args):
            "value": res["scale_up_padded"]["ms"], "higher_is_better": False, "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "data": "synthetic", "dtype": "u16",
            "config": {"workload": f"{w.name}: {w.n_layers} layers, hidden {w.hidden}, ffn "
-                                  f"{w.ffn_dim}, T = {T}, 2 MiB pages, target rank 1 / 0"},
+                                  f"{w.ffn_dim}" + (f" x {w.n_experts} experts" if w.n_experts else
+                                                    f", T = {T}") + ", 2 MiB pages, target rank 1 / 0"},
            "results": res,
            "scale_up_time_saved": round(1 - res["scale_up_padded"]["ms"] / up["ms"], 4)}
     print(json.dumps(out), flush=True)
@@ -622,9 +633,11 @@ def cpu_baseline(w, lens, table, src_pool_blocks, dst_pool_blocks, lay_s, lay_d)
 
     w_layers = max(1, min(w.n_layers, int(800e6 // max(1, _layer_bytes(w)))))
     m = oracle.Model(w_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim)
-    n = oracle.shard_elems(m, w.src_tp)
+    moe = oracle.Moe(w.n_experts) if w.n_experts else None
+    n = oracle.moe_shard_elems(m, moe, False, w.src_tp) if moe else oracle.shard_elems(m, w.src_tp)
     src = [wl.random_bits(n, seed=11 + s) for s in range(w.src_tp)]
-    dst = np.zeros(oracle.shard_elems(m, w.dst_tp), dtype=np.uint16)
+    dst = np.zeros(oracle.moe_shard_elems(m, moe, False, w.dst_tp) if moe
+                   else oracle.shard_elems(m, w.dst_tp), dtype=np.uint16)
     kv = oracle.KV(kv_layers=1, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
                    block_tokens=w.block_tokens, num_seqs=w.num_seqs,
                    max_blocks_per_seq=table.shape[1], src_pool_blocks=src_pool_blocks,
@@ -640,7 +653,10 @@ def cpu_baseline(w, lens, table, src_pool_blocks, dst_pool_blocks, lay_s, lay_d)
     budget_s, max_reps = 12.0, 64
     while reps < max_reps and t_w + t_kv < budget_s:
         t0 = time.perf_counter()
-        st, dst = oracle.reshard_weights(m, w.src_tp, w.dst_tp, w.dst_rank, src, dst)
+        if moe:
+            st, dst = oracle.reshard_weights_moe(m, moe, w.src_tp, w.dst_tp, w.dst_rank, src, dst)
+        else:
+            st, dst = oracle.reshard_weights(m, w.src_tp, w.dst_tp, w.dst_rank, src, dst)
         t_w += time.perf_counter() - t0
         assert st == oracle.OK
         bytes_w += 2 * dst.nbytes
@@ -660,7 +676,8 @@ def cpu_baseline(w, lens, table, src_pool_blocks, dst_pool_blocks, lay_s, lay_d)
 
 
 def _layer_bytes(w):
-    per = (2 * w.n_q_heads + 2 * w.n_kv_heads) * w.head_dim * w.hidden + 3 * w.hidden * w.ffn_dim
+    per = (2 * w.n_q_heads + 2 * w.n_kv_heads) * w.head_dim * w.hidden + \
+        3 * w.hidden * w.ffn_dim * max(1, w.n_experts)
     return per * w.elem_bytes // w.dst_tp
 
 

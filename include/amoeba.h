@@ -120,9 +120,28 @@ typedef struct {
    * the three pad_* fields are ignored. */
   int32_t w_layout_src, w_layout_dst;
   int32_t pad_max_tp;      /* T: finest TP degree of the model's TP set; src_tp, dst_tp | T */
-  int32_t pad_reserved;    /* 0 */
+  int32_t n_experts;       /* 0: dense FFN; E > 0: mixture of experts, see below           */
   int64_t pad_page_bytes;  /* allocation granule the partitions are aligned to (2 MiB)    */
 } amoeba_model_shape;
+
+/*
+ * Mixture-of-experts models (Sec. 3.2, "Supporting EP transformation"; the TPkEPk
+ * configurations of Sec. 4.3).  With n_experts = E > 0 the attention tensors are cut by
+ * head as above and the FFN is stored expert by expert: ffn_dim is one expert's
+ * intermediate size f, every expert has Wg_e[f, hidden], Wu_e[f, hidden], Wd_e[hidden, f],
+ * and rank r at degree t owns the whole experts [r*E/t, (r+1)*E/t) (contiguous ranges, the
+ * head rule applied to experts).  Its shard is, per layer,
+ *     AMOEBA_W_DENSE     : [qkv_r | o_r] then [gate_e | up_e | down_e] for each owned e
+ *     AMOEBA_W_FFN_PADDED: [qkv_r | o_r | 0 up to a page] then [gate_e | up_e | down_e | 0],
+ *                          every expert starting on a multiple of pad_page_bytes: experts
+ *                          are released whole, so no other boundary needs a page
+ *                          (pad_max_tp is ignored)
+ * so a target rank's experts are one contiguous byte range of one source rank whenever
+ * src_tp divides dst_tp (amoeba_plan_ffn_view: release the rest, copy nothing), and whole
+ * experts are gathered from several ranks otherwise.  Replicated tensors (router, norms)
+ * are on every rank already and are not part of a shard.  The degrees must divide E; they
+ * need not divide ffn_dim.
+ */
 
 typedef struct amoeba_plan_s amoeba_plan_t;
 
@@ -137,7 +156,8 @@ typedef struct amoeba_plan_s amoeba_plan_t;
  * Returns NULL and sets amoeba_last_error() if: a size is not positive (num_seqs,
  * max_blocks_per_seq and the pool sizes may be 0), dst_rank is outside
  * [0, dst_tp), either TP degree exceeds AMOEBA_MAX_TP or does not divide
- * n_q_heads, n_kv_heads and ffn_dim (fewer KV heads than ranks, i.e. head
+ * n_q_heads, n_kv_heads and ffn_dim (n_experts instead of ffn_dim for a
+ * mixture-of-experts model; fewer KV heads than ranks, i.e. head
  * replication, is unsupported), n_q_heads is not a multiple of n_kv_heads,
  * a layout or elem_bytes is unknown, or a pool has more than 2^31-1 blocks.
  */
@@ -250,8 +270,17 @@ int amoeba_plan_padded_info(const amoeba_plan_t* plan, int side, int64_t out[6])
  * and src_tp divides dst_tp, the target's FFN partitions are one page-aligned byte range of
  * every layer of source rank out[0]: out = {source rank, byte offset of the range inside a
  * source layer, bytes of the range, source layer bytes}.  Returns 1 if such a view exists,
- * else 0.  (The attention part is re-sliced by head and is not a view.) */
+ * else 0.  (The attention part is re-sliced by head and is not a view.)  For a
+ * mixture-of-experts plan the view is the target's expert range and exists whenever src_tp
+ * divides dst_tp and both sides use the same weight layout (Sec. 3.2, EP discussion:
+ * unused experts are freed directly); it is page aligned in the padded layout. */
 int amoeba_plan_ffn_view(const amoeba_plan_t* plan, int64_t out[4]);
+/* Expert geometry of one side of a mixture-of-experts plan (bytes): out = {experts per
+ * rank, offset of the first expert in a layer, one expert tensor, stride from one expert
+ * to the next}; an expert is three such tensors back to back (gate, up, down) and the
+ * stride is their size, rounded up to a page in the padded layout.
+ * AMOEBA_ERR_INVALID_ARG for a dense model. */
+int amoeba_plan_expert_info(const amoeba_plan_t* plan, int side, int64_t out[4]);
 /* Strides, in elements, of (head, K/V, token, d) inside one block, and the block
  * size: what an attention kernel needs to read either layout unchanged
  * (Sec. 3.1, kv_stride_order()).  out[0..3] = strides, out[4] = block elements. */

@@ -280,7 +280,7 @@ def moe_shard_elems(m: Model, x: Moe, padded: bool, tp: int) -> int:
 
 
 def moe_geometry(m: Model, x: Moe, padded: bool, tp: int):
-    """(experts per rank, first expert offset, tensor, tensor stride, layer) in elements."""
+    """(experts per rank, first expert offset, tensor, expert stride, layer) in elements."""
     out = (ctypes.c_int64 * 5)()
     st = lib().ao_moe_geometry(ctypes.byref(m._c()), ctypes.byref(x._c()), int(padded), tp, out)
     assert st == OK

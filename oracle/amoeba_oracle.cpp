@@ -387,8 +387,8 @@ bool moe_ok(const ao_model* m, const ao_moe* x, int tp) {
 struct MoeGeom {
   int64_t own;      // experts per rank
   int64_t first;    // element offset of the first expert tensor in a layer
-  int64_t tensor;   // elements of one expert tensor
-  int64_t slot;     // elements from one expert tensor to the next
+  int64_t tensor;   // elements of one expert tensor (gate, up and down are equal in size)
+  int64_t slot;     // elements from one expert to the next: 3 tensors, rounded up to a page
   int64_t layer;
 };
 
@@ -399,8 +399,8 @@ MoeGeom moe_geom(const ao_model* m, const ao_moe* x, bool padded, int tp) {
   g.own = x->n_experts / tp;
   g.first = (attn + page - 1) / page * page;
   g.tensor = (int64_t)m->ffn_dim * m->hidden;
-  g.slot = (g.tensor + page - 1) / page * page;
-  g.layer = g.first + g.own * 3 * g.slot;
+  g.slot = (3 * g.tensor + page - 1) / page * page;
+  g.layer = g.first + g.own * g.slot;
   return g;
 }
 
@@ -442,8 +442,8 @@ int reshard_weights_moe_t(const ao_model* m, const ao_moe* x, int k, int kp, int
       const int64_t js = ex % gs.own;            // its position on that rank
       for (int64_t w = 0; w < 3; ++w)            // gate, up, down
         for (int64_t i = 0; i < gd.tensor; ++i)
-          dst[db + gd.first + (j * 3 + w) * gd.slot + i] =
-              src[s][sb + gs.first + (js * 3 + w) * gs.slot + i];
+          dst[db + gd.first + j * gd.slot + w * gd.tensor + i] =
+              src[s][sb + gs.first + js * gs.slot + w * gs.tensor + i];
     }
   }
   return AO_OK;

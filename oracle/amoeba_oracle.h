@@ -153,7 +153,8 @@ int ao_reshard_weights_padded(const ao_model* m, const ao_pad* pad, int src_tp, 
  * not print the expert-to-rank rule; contiguous ranges, like its head rule).  Per layer a
  * rank stores [qkv_r | o_r] and then, for each owned expert in order, [gate_e][up_e][down_e].
  * On a padded side (page_bytes > 0 and the side's flag set) the attention part is rounded up
- * to a page and every expert tensor starts on a page boundary, the gaps holding zeros. */
+ * to a page and every expert starts on a page boundary (experts are released whole, so that
+ * is the only boundary a release can fall on), the gaps holding zeros. */
 typedef struct {
   int32_t n_experts;
   int32_t src_padded, dst_padded;
@@ -162,8 +163,8 @@ typedef struct {
 
 /* Elements of one rank's shard at degree tp, all layers; -1 if unsupported. */
 int64_t ao_moe_shard_elems(const ao_model* m, const ao_moe* x, int padded, int tp);
-/* out = {experts per rank, offset of the first expert tensor, expert tensor elems, stride
- *        between expert tensors, layer elems}, in elements. */
+/* out = {experts per rank, offset of the first expert, expert tensor elems, stride between
+ *        experts, layer elems}, in elements. */
 int ao_moe_geometry(const ao_model* m, const ao_moe* x, int padded, int tp, int64_t out[5]);
 /* dst <- rank dst_rank's shard at degree dst_tp (attention TP, experts EP), gathered from the
  * src_tp shards; gaps of a padded destination are zero-filled. */

@@ -36,7 +36,7 @@ EXPORTS = [
     "amoeba_plan_kv_stride_order", "amoeba_plan_num_segments", "amoeba_plan_segment",
     "amoeba_plan_tune", "amoeba_copy_baseline", "amoeba_last_error",
     "amoeba_merge_kv_inplace", "amoeba_merge_kv_status", "amoeba_plan_merge_factor",
-    "amoeba_plan_padded_info", "amoeba_plan_ffn_view",
+    "amoeba_plan_padded_info", "amoeba_plan_ffn_view", "amoeba_plan_expert_info",
 ]
 
 
@@ -47,7 +47,7 @@ class _Shape(ctypes.Structure):
                  "num_seqs", "max_blocks_per_seq")] + \
                [("src_pool_blocks", ctypes.c_int64), ("dst_pool_blocks", ctypes.c_int64),
                 ("w_layout_src", ctypes.c_int32), ("w_layout_dst", ctypes.c_int32),
-                ("pad_max_tp", ctypes.c_int32), ("pad_reserved", ctypes.c_int32),
+                ("pad_max_tp", ctypes.c_int32), ("n_experts", ctypes.c_int32),
                 ("pad_page_bytes", ctypes.c_int64)]
 
 
@@ -72,7 +72,7 @@ class ModelShape:
     w_layout_src: int = 0
     w_layout_dst: int = 0
     pad_max_tp: int = 0
-    pad_reserved: int = 0
+    n_experts: int = 0
     pad_page_bytes: int = 0
 
     def _c(self) -> _Shape:
@@ -133,6 +133,8 @@ def lib() -> ctypes.CDLL:
     L.amoeba_plan_merge_factor.argtypes = [vp]
     L.amoeba_plan_padded_info.restype = i32
     L.amoeba_plan_padded_info.argtypes = [vp, i32, ctypes.POINTER(i64)]
+    L.amoeba_plan_expert_info.restype = i32
+    L.amoeba_plan_expert_info.argtypes = [vp, i32, ctypes.POINTER(i64)]
     L.amoeba_plan_ffn_view.restype = i32
     L.amoeba_plan_ffn_view.argtypes = [vp, ctypes.POINTER(i64)]
     L.amoeba_last_error.restype = ctypes.c_char_p
@@ -320,6 +322,16 @@ def amoeba_plan_padded_info(plan: Plan, side: int):
     """(attn, attn_padded, part, part_padded, stride, layer) in bytes for a padded side."""
     out = (ctypes.c_int64 * 6)()
     rc = lib().amoeba_plan_padded_info(plan.handle, side, out)
+    if rc != OK:
+        raise AmoebaError(rc, amoeba_last_error())
+    return tuple(int(x) for x in out)
+
+
+def amoeba_plan_expert_info(plan: Plan, side: int):
+    """(experts per rank, first expert offset, expert tensor bytes, expert stride) of a
+    mixture-of-experts plan's side, in bytes."""
+    out = (ctypes.c_int64 * 4)()
+    rc = lib().amoeba_plan_expert_info(plan.handle, side, out)
     if rc != OK:
         raise AmoebaError(rc, amoeba_last_error())
     return tuple(int(x) for x in out)

@@ -214,12 +214,30 @@ int amoeba_plan_tensor_info(const amoeba_plan_t* plan, int side, int tensor, int
   if (rows) *rows = L.rows[tensor];
   if (cols) *cols = L.cols[tensor];
   if (layer_elems) *layer_elems = L.layer_elems;
+  if (plan->shape.n_experts > 0) {  // gate/up/down: the first owned expert's tensors
+    const amoeba::ExpertGeom& g = side ? plan->exp_dst : plan->exp_src;
+    const int64_t e = plan->shape.elem_bytes;
+    if (elem_off && tensor >= AMOEBA_T_GATE)
+      *elem_off = (g.first + (tensor - AMOEBA_T_GATE) * g.tensor) / e;
+    if (layer_elems) *layer_elems = g.layer / e;
+  }
+  return AMOEBA_OK;
+}
+
+int amoeba_plan_expert_info(const amoeba_plan_t* plan, int side, int64_t out[4]) {
+  if (!plan || !out || (side != 0 && side != 1) || plan->shape.n_experts <= 0) {
+    set_error("amoeba_plan_expert_info: bad plan, side or out, or the model has no experts");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  const amoeba::ExpertGeom& g = side ? plan->exp_dst : plan->exp_src;
+  out[0] = g.own; out[1] = g.first; out[2] = g.tensor; out[3] = g.slot;
   return AMOEBA_OK;
 }
 
 int amoeba_plan_padded_info(const amoeba_plan_t* plan, int side, int64_t out[6]) {
-  if (!plan || !out || (side != 0 && side != 1) || !(side ? plan->dst_padded : plan->src_padded)) {
-    set_error("amoeba_plan_padded_info: bad plan, side or out, or that side is dense");
+  if (!plan || !out || (side != 0 && side != 1) || !(side ? plan->dst_padded : plan->src_padded) ||
+      plan->shape.n_experts > 0) {
+    set_error("amoeba_plan_padded_info: bad plan, side or out, or that side is dense or expert-wise");
     return AMOEBA_ERR_INVALID_ARG;
   }
   const amoeba::PaddedGeom& g = side ? plan->pad_dst : plan->pad_src;
@@ -229,7 +247,18 @@ int amoeba_plan_padded_info(const amoeba_plan_t* plan, int side, int64_t out[6])
 }
 
 int amoeba_plan_ffn_view(const amoeba_plan_t* plan, int64_t out[4]) {
-  if (!plan || !out || !plan->src_padded || !plan->dst_padded || plan->kp % plan->k) return 0;
+  if (!plan || !out || plan->kp % plan->k) return 0;
+  if (plan->shape.n_experts > 0) {  // the target's experts inside their one source rank
+    if (plan->src_padded != plan->dst_padded) return 0;
+    const amoeba::ExpertGeom& S = plan->exp_src;
+    const int64_t own = plan->exp_dst.own, host = int64_t(plan->rp) * plan->k / plan->kp;
+    out[0] = host;
+    out[1] = S.first + (int64_t(plan->rp) * own - host * S.own) * S.slot;
+    out[2] = own * S.slot;
+    out[3] = S.layer;
+    return 1;
+  }
+  if (!plan->src_padded || !plan->dst_padded) return 0;
   const int64_t T = plan->shape.pad_max_tp;
   const int64_t host = int64_t(plan->rp) * plan->k / plan->kp;  // source rank holding the range
   const int64_t first = int64_t(plan->rp) * (T / plan->kp) - host * (T / plan->k);

@@ -19,8 +19,9 @@ namespace {
 ShardLayout shard_layout(const amoeba_model_shape& s, int tp) {
   ShardLayout L;
   const int64_t H = s.hidden, d = s.head_dim;
+  const bool moe = s.n_experts > 0;  // then gate/up/down describe the first owned expert
   const int64_t q = int64_t(s.n_q_heads) * d / tp, kv = int64_t(s.n_kv_heads) * d / tp,
-                f = int64_t(s.ffn_dim) / tp;
+                f = moe ? int64_t(s.ffn_dim) : int64_t(s.ffn_dim) / tp;
   const int64_t rows[AMOEBA_T_COUNT] = {q, kv, kv, H, f, f, H};
   const int64_t cols[AMOEBA_T_COUNT] = {H, H, H, q, H, H, f};
   int64_t at = 0;
@@ -30,6 +31,7 @@ ShardLayout shard_layout(const amoeba_model_shape& s, int tp) {
     L.cols[t] = cols[t];
     at += rows[t] * cols[t];
   }
+  if (moe) at += (int64_t(s.n_experts) / tp - 1) * 3 * f * H;
   L.layer_elems = at;
   return L;
 }
@@ -61,17 +63,22 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
     return fail(err, "a pool has more than 2^31-1 blocks (block ids are int32)");
   for (int tp : {k, kp}) {
     if (tp < 1 || tp > AMOEBA_MAX_TP) return fail(err, "TP degree outside [1, 16]");
-    if (s.n_q_heads % tp || s.n_kv_heads % tp || s.ffn_dim % tp)
-      return fail(err, "TP degree must divide n_q_heads, n_kv_heads and ffn_dim");
+    if (s.n_q_heads % tp || s.n_kv_heads % tp)
+      return fail(err, "TP degree must divide n_q_heads and n_kv_heads");
+    if (s.n_experts > 0 ? s.n_experts % tp : s.ffn_dim % tp)
+      return fail(err, s.n_experts > 0 ? "TP/EP degree must divide n_experts"
+                                       : "TP degree must divide ffn_dim");
   }
+  if (s.n_experts < 0) return fail(err, "n_experts is negative");
+  const bool moe = s.n_experts > 0;
   if (rp < 0 || rp >= kp) return fail(err, "dst_rank outside [0, dst_tp)");
   for (int lay : {s.w_layout_src, s.w_layout_dst})
     if (lay != AMOEBA_W_DENSE && lay != AMOEBA_W_FFN_PADDED)
       return fail(err, "unknown weight layout");
   const bool any_padded = s.w_layout_src == AMOEBA_W_FFN_PADDED || s.w_layout_dst == AMOEBA_W_FFN_PADDED;
   if (any_padded) {
-    if (s.pad_max_tp < 1 || s.pad_max_tp > AMOEBA_MAX_TP || s.ffn_dim % s.pad_max_tp ||
-        s.pad_max_tp % k || s.pad_max_tp % kp)
+    if (!moe && (s.pad_max_tp < 1 || s.pad_max_tp > AMOEBA_MAX_TP || s.ffn_dim % s.pad_max_tp ||
+        s.pad_max_tp % k || s.pad_max_tp % kp))
       return fail(err, "pad_max_tp must be in [1, 16], divide ffn_dim and be a multiple of both TP degrees");
     if (s.pad_page_bytes < s.elem_bytes || s.pad_page_bytes % s.elem_bytes)
       return fail(err, "pad_page_bytes must be a positive multiple of elem_bytes");
@@ -92,7 +99,7 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
   p->dst_padded = s.w_layout_dst == AMOEBA_W_FFN_PADDED;
   p->src_layer_bytes = p->src_layout.layer_elems * e;
   p->dst_layer_bytes = p->dst_layout.layer_elems * e;
-  if (any_padded) {
+  if (any_padded && !moe) {
     const int64_t G = s.pad_page_bytes, T = s.pad_max_tp;
     auto pages = [G](int64_t bytes) { return (bytes + G - 1) / G * G; };
     auto padded_geom = [&](const ShardLayout& L, int tp) {
@@ -116,7 +123,7 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
                                         s.ffn_dim,                 s.ffn_dim,
                                         s.ffn_dim};
   for (int t = 0; t < AMOEBA_T_COUNT; ++t) {
-    if (any_padded && t >= AMOEBA_T_GATE) break;  // FFN tensors: per partition, below
+    if ((any_padded || moe) && t >= AMOEBA_T_GATE) break;  // FFN tensors: below
     const bool cut_on_rows = (t != AMOEBA_T_O && t != AMOEBA_T_DOWN);
     const int64_t N = axis[t], per_src = N / k, per_dst = N / kp;
     const int64_t want_lo = rp * per_dst, want_hi = want_lo + per_dst;
@@ -151,7 +158,72 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
     }
   }
 
-  if (any_padded) {
+  if (moe) {
+    // Sec. 3.2, EP discussion: the FFN is stored expert by expert and whole experts change
+    // owner.  The target's expert range is intersected with every source rank's range; the
+    // experts of an intersection are equally spaced on both sides, so they form one
+    // rectangle (one contiguous range when neither side has gaps).
+    auto geom = [&](const ShardLayout& L, int tp, bool padded) {
+      ExpertGeom g;
+      const int64_t G = s.pad_page_bytes;
+      g.own = int64_t(s.n_experts) / tp;
+      g.first = L.off[AMOEBA_T_GATE] * e;
+      g.tensor = int64_t(s.ffn_dim) * s.hidden * e;
+      g.slot = 3 * g.tensor;
+      if (padded) {
+        g.first = (g.first + G - 1) / G * G;
+        g.slot = (g.slot + G - 1) / G * G;
+      }
+      g.layer = g.first + g.own * g.slot;
+      return g;
+    };
+    p->exp_src = geom(p->src_layout, k, p->src_padded);
+    p->exp_dst = geom(p->dst_layout, kp, p->dst_padded);
+    p->src_layer_bytes = p->exp_src.layer;
+    p->dst_layer_bytes = p->exp_dst.layer;
+    const ExpertGeom &S = p->exp_src, &D = p->exp_dst;
+    const int64_t attn = p->dst_layout.off[AMOEBA_T_GATE] * e;
+    if (D.first > attn) {
+      Segment z{};
+      z.src_rank = -1;
+      z.part = 0;
+      z.dst_off = attn;
+      z.rows = 1;
+      z.run = z.src_pitch = z.dst_pitch = D.first - attn;
+      p->segments.push_back(z);
+    }
+    const int64_t want_lo = rp * D.own, want_hi = want_lo + D.own;
+    for (int r = 0; r < k; ++r) {
+      const int64_t lo = std::max(want_lo, r * S.own), hi = std::min(want_hi, (r + 1) * S.own);
+      if (lo >= hi) continue;
+      Segment g;
+      g.src_rank = r;
+      g.part = 1;
+      g.src_off = S.first + (lo - r * S.own) * S.slot;
+      g.dst_off = D.first + (lo - want_lo) * D.slot;
+      g.rows = hi - lo;
+      g.run = 3 * S.tensor;
+      g.src_pitch = S.slot;
+      g.dst_pitch = D.slot;
+      if (g.run == g.src_pitch && g.run == g.dst_pitch) {
+        g.run *= g.rows;
+        g.rows = 1;
+        g.src_pitch = g.dst_pitch = g.run;
+      }
+      p->segments.push_back(g);
+      p->weight_rank_mask |= 1u << r;
+      if (D.slot > 3 * D.tensor) {  // gaps behind every expert of a padded target
+        Segment z{};
+        z.src_rank = -1;
+        z.part = 1;
+        z.dst_off = g.dst_off + 3 * D.tensor;
+        z.rows = hi - lo;
+        z.run = D.slot - 3 * D.tensor;
+        z.src_pitch = z.dst_pitch = D.slot;
+        p->segments.push_back(z);
+      }
+    }
+  } else if (any_padded) {
     // Sec. 3.2, Improvement 1.  Walk the finest partitions the target rank owns; each one
     // lives on exactly one source rank.  On a padded side a tensor-partition is one
     // contiguous, page-aligned range; on a dense side gate/up partitions are row ranges of

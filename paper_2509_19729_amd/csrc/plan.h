@@ -39,6 +39,15 @@ struct PaddedGeom {
   int64_t layer;
 };
 
+// Expert-wise FFN layout of one side of a mixture-of-experts plan, in bytes.
+struct ExpertGeom {
+  int64_t own;     // experts per rank
+  int64_t first;   // offset of the first expert tensor in a layer
+  int64_t tensor;  // one expert tensor (gate, up and down are equal in size)
+  int64_t slot;    // from one expert to the next: 3 tensors, rounded up to a page if padded
+  int64_t layer;
+};
+
 struct Tuning {
   int w_grid = 0, w_unroll = 0, w_threads = 0, kv_grid = 0, kv_unroll = 0, kv_threads = 0,
       nontemporal = 0, kv_staged = 0, kv_blocks_hint = 0, w_part = 0;
@@ -52,7 +61,8 @@ struct amoeba_plan_s {
   amoeba::ShardLayout src_layout, dst_layout;
   std::vector<amoeba::Segment> segments;  // one layer's worth, target order; src_rank -1 = zeros
   bool src_padded, dst_padded;
-  amoeba::PaddedGeom pad_src, pad_dst;     // valid where the side is padded
+  amoeba::PaddedGeom pad_src, pad_dst;     // valid where the side is padded (dense FFN)
+  amoeba::ExpertGeom exp_src, exp_dst;     // valid when shape.n_experts > 0
   int64_t src_layer_bytes, dst_layer_bytes;
   uint32_t weight_rank_mask, kv_rank_mask;
   // KV geometry

@@ -40,6 +40,7 @@ class Workload:
     lengths: str              # recipe name, see seq_lens()
     placement: str            # recipe name, see block_placement()
     elem_bytes: int = 2
+    n_experts: int = 0        # > 0: mixture of experts, ffn_dim is one expert's intermediate size
 
     def scaled(self, **kw) -> "Workload":
         return replace(self, **kw)
@@ -56,6 +57,10 @@ WORKLOADS = {
                        "lognormal_2k_16k", "freelist_rr"),
     "long8b": Workload("long8b", 5, 32, 4096, 32, 8, 128, 14336, "bf16", 1, 4, 3, 16, 64,
                        "long32k_pareto", "random105"),
+    # outside the five benchmark configurations: the mixture-of-experts shape of the paper's
+    # EP experiment (Sec. 4.3, 4 x (TP1 EP1) -> TP4 EP4), 128 experts of 768 x 2048
+    "qwen3moe": Workload("qwen3moe", 6, 48, 2048, 32, 4, 128, 768, "bf16", 1, 4, 1, 16, 64,
+                         "lognormal_1k_8k", "freelist_rr", n_experts=128),
 }
 ORDER = ["tiny", "llama7b", "llama13b", "gqa70b", "long8b"]
 

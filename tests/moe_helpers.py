@@ -4,7 +4,7 @@ split / slicing / concatenate only (nothing here is imported by the oracle or th
 Attention tensors are cut by head with ``np.split`` as for a dense model; rank r at degree t
 keeps the whole experts ``experts[r*E/t:(r+1)*E/t]`` (Sec. 3.2, EP discussion), each stored as
 gate, up, down one after the other; with ``page_elems`` > 0 the attention part and every expert
-tensor are padded with zeros to a multiple of it.
+are padded with zeros to a multiple of it.
 """
 from __future__ import annotations
 
@@ -54,5 +54,5 @@ def moe_shard_of(layers, tp, rank, n_experts, page_elems=0):
                 np.ascontiguousarray(np.split(L["o"], tp, axis=1)[rank])]
         parts.append(_pad(np.concatenate([a.ravel() for a in attn]), page_elems))
         for g, u, dn in L["experts"][rank * own:(rank + 1) * own]:
-            parts += [_pad(g, page_elems), _pad(u, page_elems), _pad(dn, page_elems)]
+            parts.append(_pad(np.concatenate([g.ravel(), u.ravel(), dn.ravel()]), page_elems))
     return np.concatenate(parts)

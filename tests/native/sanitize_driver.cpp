@@ -26,6 +26,32 @@ static std::vector<uint16_t> random_u16(size_t n, uint64_t seed) {
   return v;
 }
 
+// Applies the plan's segment table to host buffers with explicit bounds checks; every target
+// byte must be written exactly once and the result must equal `want`.
+static void apply_and_compare(const amoeba_plan_s& plan, const amoeba_model_shape& s,
+                              const std::vector<std::vector<uint16_t>>& src, int k,
+                              const std::vector<uint16_t>& want) {
+  const size_t dst_bytes = size_t(plan.dst_layer_bytes) * s.n_layers;
+  const size_t src_bytes = size_t(plan.src_layer_bytes) * s.n_layers;
+  std::vector<uint8_t> got(dst_bytes, 0xEE), hits(dst_bytes, 0);
+  for (const amoeba::Segment& g : plan.segments)
+    for (int l = 0; l < s.n_layers; ++l)
+      for (int64_t row = 0; row < g.rows; ++row) {
+        const int64_t b = l * plan.dst_layer_bytes + g.dst_off + row * g.dst_pitch;
+        CHECK(b >= 0 && size_t(b + g.run) <= dst_bytes);
+        if (g.src_rank < 0) {
+          std::memset(got.data() + b, 0, size_t(g.run));
+        } else {
+          const int64_t a = l * plan.src_layer_bytes + g.src_off + row * g.src_pitch;
+          CHECK(g.src_rank < k && a >= 0 && size_t(a + g.run) <= src_bytes);
+          std::memcpy(got.data() + b, reinterpret_cast<const uint8_t*>(src[g.src_rank].data()) + a, size_t(g.run));
+        }
+        for (int64_t i = 0; i < g.run; ++i) ++hits[size_t(b + i)];
+      }
+  for (size_t i = 0; i < dst_bytes; ++i) if (hits[i] != 1) { CHECK(hits[i] == 1); break; }
+  CHECK(std::memcmp(got.data(), want.data(), dst_bytes) == 0);
+}
+
 static void weights_case(int k, int kp, bool sp, bool dp, int T, int64_t page) {
   amoeba_model_shape s;
   std::memset(&s, 0, sizeof(s));
@@ -55,29 +81,43 @@ static void weights_case(int k, int kp, bool sp, bool dp, int T, int64_t page) {
     amoeba_plan_s plan;
     std::string err;
     CHECK(amoeba::build_plan(&plan, &s, k, kp, rp, &err));
-    const size_t dst_bytes = size_t(plan.dst_layer_bytes) * s.n_layers;
-    const size_t src_bytes = size_t(plan.src_layer_bytes) * s.n_layers;
-    CHECK(src_bytes == src[0].size() * 2);
-    std::vector<uint16_t> want(dst_bytes / 2, 0xEEEE);
+    CHECK(size_t(plan.src_layer_bytes) * s.n_layers == src[0].size() * 2);
+    std::vector<uint16_t> want(size_t(plan.dst_layer_bytes) * s.n_layers / 2, 0xEEEE);
     if (padded) CHECK(ao_reshard_weights_padded(&m, &pad, k, kp, rp, src_ptr.data(), want.data()) == AO_OK);
     else CHECK(ao_reshard_weights(&m, k, kp, rp, src_ptr.data(), want.data()) == AO_OK);
-    std::vector<uint8_t> got(dst_bytes, 0xEE), hits(dst_bytes, 0);
-    for (const amoeba::Segment& g : plan.segments)
-      for (int l = 0; l < s.n_layers; ++l)
-        for (int64_t row = 0; row < g.rows; ++row) {
-          const int64_t b = l * plan.dst_layer_bytes + g.dst_off + row * g.dst_pitch;
-          CHECK(b >= 0 && size_t(b + g.run) <= dst_bytes);
-          if (g.src_rank < 0) {
-            std::memset(got.data() + b, 0, size_t(g.run));
-          } else {
-            const int64_t a = l * plan.src_layer_bytes + g.src_off + row * g.src_pitch;
-            CHECK(g.src_rank < k && a >= 0 && size_t(a + g.run) <= src_bytes);
-            std::memcpy(got.data() + b, reinterpret_cast<const uint8_t*>(src[g.src_rank].data()) + a, size_t(g.run));
-          }
-          for (int64_t i = 0; i < g.run; ++i) ++hits[size_t(b + i)];
-        }
-    for (size_t i = 0; i < dst_bytes; ++i) if (hits[i] != 1) { CHECK(hits[i] == 1); break; }
-    CHECK(std::memcmp(got.data(), want.data(), dst_bytes) == 0);
+    apply_and_compare(plan, s, src, k, want);
+  }
+}
+
+static void moe_case(int k, int kp, bool sp, bool dp, int64_t page) {
+  amoeba_model_shape s;
+  std::memset(&s, 0, sizeof(s));
+  s.n_layers = 2; s.hidden = 12; s.n_q_heads = 8; s.n_kv_heads = 8; s.head_dim = 2; s.ffn_dim = 5;
+  s.elem_bytes = 2; s.kv_block_tokens = 4; s.kv_layers = 1; s.n_experts = 8;
+  s.w_layout_src = sp; s.w_layout_dst = dp; s.pad_page_bytes = page;
+  ao_model m = {s.n_layers, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn_dim, 2};
+  ao_moe flat = {8, 0, 0, 0}, up = {8, 0, 1, page}, x = {8, sp, dp, page};
+  std::vector<std::vector<uint16_t>> dense(k), src(k);
+  std::vector<const void*> dense_ptr(k), src_ptr(k);
+  for (int r = 0; r < k; ++r) { dense[r] = random_u16(size_t(ao_moe_shard_elems(&m, &flat, 0, k)), 11 * r + k); dense_ptr[r] = dense[r].data(); }
+  for (int r = 0; r < k; ++r) {
+    if (sp) {
+      src[r].assign(size_t(ao_moe_shard_elems(&m, &up, 1, k)), 0xEEEE);
+      CHECK(ao_reshard_weights_moe(&m, &up, k, k, r, dense_ptr.data(), src[r].data()) == AO_OK);
+    } else {
+      src[r] = dense[r];
+    }
+    src_ptr[r] = src[r].data();
+  }
+  for (int rp = 0; rp < kp; ++rp) {
+    amoeba_plan_s plan;
+    std::string err;
+    CHECK(amoeba::build_plan(&plan, &s, k, kp, rp, &err));
+    CHECK(size_t(plan.src_layer_bytes) * s.n_layers == src[0].size() * 2);
+    std::vector<uint16_t> want(size_t(plan.dst_layer_bytes) * s.n_layers / 2, 0xEEEE);
+    CHECK(want.size() == size_t(ao_moe_shard_elems(&m, &x, dp, kp)));
+    CHECK(ao_reshard_weights_moe(&m, &x, k, kp, rp, src_ptr.data(), want.data()) == AO_OK);
+    apply_and_compare(plan, s, src, k, want);
   }
 }
 
@@ -129,6 +169,10 @@ int main() {
     weights_case(t[0], t[1], false, true, 4, 64);
     weights_case(t[0], t[1], true, true, 4, 1000);
     weights_case(t[0], t[1], true, false, 8, 128);
+    moe_case(t[0], t[1], false, false, 0);
+    moe_case(t[0], t[1], false, true, 64);
+    moe_case(t[0], t[1], true, true, 1000);
+    moe_case(t[0], t[1], true, false, 64);
     for (int ls = 0; ls < 2; ++ls) for (int ld = 0; ld < 2; ++ld) kv_case(t[0], t[1], ls, ld);
   }
   merge_case(4, 1); merge_case(2, 2); merge_case(2, 1);

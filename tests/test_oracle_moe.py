@@ -86,8 +86,8 @@ def test_scale_up_is_a_contiguous_range_of_one_source_rank():
             for rp in range(kp):
                 host = rp * k // kp
                 st, dst = oracle.reshard_weights_moe(MODEL, x, k, kp, rp, src)
-                lo = first_s + (rp * own_d - host * own_s) * 3 * slot
-                n = own_d * 3 * slot
+                lo = first_s + (rp * own_d - host * own_s) * slot
+                n = own_d * slot
                 if page:
                     assert lo % pe == 0 and n % pe == 0 and first_d % pe == 0
                 np.testing.assert_array_equal(
@@ -113,9 +113,9 @@ def test_expert_pages_reproduce_table_2():
         for tp, want in ((1, float(p1)), (4, float(p4))):
             own, first, tensor, slot, layer = oracle.moe_geometry(m, x, True, tp)
             assert own * tensor * 2 / page == pytest.approx(want, abs=1e-3), name
-            # an expert tensor of 7.91 pages occupies 8: below one page of waste per tensor
-            assert slot * 2 % page == 0 and 0 <= (slot - tensor) * 2 < page
-            assert layer == first + own * 3 * slot and first * 2 % page == 0
+            # an expert of 3 x 7.91 pages occupies 24: below one page of waste per expert
+            assert slot * 2 % page == 0 and 0 <= (slot - 3 * tensor) * 2 < page
+            assert layer == first + own * slot and first * 2 % page == 0
     assert rows == 2
 
 
@@ -160,10 +160,10 @@ def test_routed_ffn_from_resharded_ranks_equals_the_unsharded_one():
             w = sh.view(np.float32).astype(np.float64)
             for j in range(own):
                 ex = rp * own + j
-                at = first + j * 3 * slot
+                at = first + j * slot
                 g = w[at:at + tensor].reshape(m.ffn_dim, m.hidden)
-                u = w[at + slot:at + slot + tensor].reshape(m.ffn_dim, m.hidden)
-                d = w[at + 2 * slot:at + 2 * slot + tensor].reshape(m.hidden, m.ffn_dim)
+                u = w[at + tensor:at + 2 * tensor].reshape(m.ffn_dim, m.hidden)
+                d = w[at + 2 * tensor:at + 3 * tensor].reshape(m.hidden, m.ffn_dim)
                 for t in range(7):
                     for c in range(2):
                         if top2[t, c] == ex:

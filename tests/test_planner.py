@@ -84,7 +84,8 @@ def test_segment_table_reproduces_the_oracle(k, kp, n_kv):
 
 def test_source_ranks_read_at_the_benchmark_configs():
     want = {"tiny": {0}, "llama7b": {2, 3}, "llama13b": {0, 1}, "gqa70b": {4, 5}, "long8b": {0}}
-    for name, w in wl.WORKLOADS.items():
+    for name in wl.ORDER:
+        w = wl.WORKLOADS[name]
         s = ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim)
         plan = ab.amoeba_plan(s, w.src_tp, w.dst_tp, w.dst_rank)
         mask = ab.amoeba_plan_src_rank_mask(plan)
