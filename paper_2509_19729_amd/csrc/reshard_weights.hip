@@ -7,8 +7,9 @@
 // this kernel is a table-driven streaming gather.
 //
 // Mapping to the machine.  The work is HBM-bound (every byte is read once and
-// written once), so: each lane moves 16 bytes per access, a workgroup of 256
-// lanes owns a tile of UNROLL x THREADS x 16 B that is contiguous in the destination,
+// written once), so: each lane moves 16 bytes per access, a workgroup of THREADS
+// lanes (one wavefront by default) owns a tile of UNROLL x THREADS x 16 B that is
+// contiguous in the destination,
 // all loads of a tile are issued before its first store, and accesses carry the
 // non-temporal hint because nothing is reused.  Measured on MI355X the best shape
 // is the smallest one: one 16-byte vector per lane and one workgroup per tile,
