@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--kv-layers", type=int, default=0,
                     help="KV layers resident per call (0 = all that fit the workload definition)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="reshard mode: also capture one step in a HIP graph and time its replays "
+                         "(what a launch-bound configuration such as `tiny` gains from it)")
     ap.add_argument("--head-dim", type=int, default=0,
                     help="override the workload's head_dim (with --kv-heads: other head geometries "
                          "on the same sequence table, e.g. 64-byte head vectors)")
@@ -232,6 +235,24 @@ def main():
         for line in open(summary):
             if line.startswith("traffic_bytes_per_launch kv_regroup_kernel:"):
                 out["roofline"]["traffic"] = int(line.split(":")[1])
+
+    if args.graph:
+        # the reshard calls only enqueue kernels (no allocation, no memset node), so a step can
+        # be captured once and replayed
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        out["config"]["graph_replay_ms_per_step"] = round(
+            (time.perf_counter() - g0) * 1e3 / args.steps, 4)
+        rc, n_blocks = ab.amoeba_kv_status(plan)
+        assert rc == ab.OK and n_blocks == total_blocks, (rc, n_blocks)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, lens, table, src_pool_blocks, dst_pool_blocks,
