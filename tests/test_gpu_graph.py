@@ -97,3 +97,57 @@ def test_weights_and_kv_replay_from_a_captured_graph():
         rc, total = ab.amoeba_kv_status(plan)      # outside the graph: it synchronises
         assert rc == ab.OK and total == int(((lens.astype(np.int64) + B - 1) // B).sum())
     plan.close()
+
+
+def test_inplace_merge_replays_from_a_captured_graph():
+    """The in-place merge clears its flags with a kernel (no memset node) and compacts its work
+    list on the device, so it can be captured too.  The pool is restored and the lengths are
+    changed eagerly between replays; every replay must match the oracle."""
+    from test_gpu_merge import instances
+
+    m, k, rp = 2, 1, 1
+    lens0 = [[33, 7, 100], [64, 1, 18]]
+    cfg, insts = instances(m, k, lens0, n_heads=4, d=64, B=16, layers=2, P=16, W=9, seed=3)
+    g = rp % m
+    plan = ab.amoeba_plan(shape_from(model_for_kv(cfg), cfg), k, k * m, rp)
+    pristine = to_dev(insts[g]["pools"][0])
+    local = pristine.clone()
+    remote = [None if g2 == g else to_dev(insts[g2]["pools"][0]) for g2 in range(m)]
+    tabs = [torch.from_numpy(i["table"]).cuda() for i in insts]
+    lens_d = [torch.from_numpy(i["lens"]).cuda() for i in insts]
+    out_table = torch.zeros((m * cfg.num_seqs, cfg.max_blocks_per_seq), dtype=torch.int32,
+                            device="cuda")
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ab.amoeba_merge_kv_inplace(plan, local, remote, tabs, lens_d, out_table)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ab.amoeba_merge_kv_inplace(plan, local, remote, tabs, lens_d, out_table)
+
+    for it in range(4):
+        lens = [i["lens"].copy() for i in insts]
+        lens[it % m][it % 3] = max(0, int(lens[it % m][it % 3]) - 9 * it)
+        for dev, host in zip(lens_d, lens):
+            dev.copy_(torch.from_numpy(host))
+        local.copy_(pristine)
+        out_table.fill_(-5)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want_pool = insts[g]["pools"][0].copy()
+        st, want_table, want_n = oracle.merge_kv_inplace(
+            cfg, k, m, rp, want_pool,
+            [None if g2 == g else insts[g2]["pools"][0] for g2 in range(m)],
+            [i["table"] for i in insts], lens)
+        assert st == oracle.OK
+        np.testing.assert_array_equal(out_table.cpu().numpy(), want_table)
+        np.testing.assert_array_equal(
+            local.cpu().numpy().view(want_pool.dtype).reshape(want_pool.shape), want_pool)
+        rc, n = ab.amoeba_merge_kv_status(plan)
+        assert rc == ab.OK and n == want_n
+    plan.close()
