@@ -92,9 +92,8 @@ amoeba_plan_t* amoeba_plan(const amoeba_model_shape* shape, int src_tp, int dst_
       p->workspace_bytes = bytes;
       if (p->merge_factor >= 2) {
         const size_t mbytes =
-            sizeof(int32_t) * amoeba::merge_workspace_ints(p->shape.num_seqs,
-                                                           p->shape.src_pool_blocks,
-                                                           p->merge_factor);
+            sizeof(int32_t) *
+            amoeba::merge_workspace_ints(p->shape.src_pool_blocks, p->merge_factor);
         void* mws = nullptr;
         const hipError_t mrc = hipMalloc(&mws, mbytes);
         if (mrc != hipSuccess) {

@@ -23,7 +23,7 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
 
 // int32 words of the merge workspace: header, chunk counts, one flag and one work-list
 // entry per new block id of the pool.
-size_t merge_workspace_ints(int64_t num_seqs, int64_t pool_blocks, int m);
+size_t merge_workspace_ints(int64_t pool_blocks, int m);
 
 int launch_merge_kv_inplace(const amoeba_plan_s* p, void* local_pool,
                             const void* const* remote_pools,

@@ -246,7 +246,7 @@ void launch_copy(bool nt, int waves, dim3 grid, hipStream_t stream, const MergeC
 
 }  // namespace
 
-size_t merge_workspace_ints(int64_t num_seqs, int64_t pool_blocks, int m) {
+size_t merge_workspace_ints(int64_t pool_blocks, int m) {
   const size_t slots = size_t(pool_blocks) * size_t(m);
   return size_t(kWsHeader) + (slots + kWide - 1) / kWide + 1 + 2 * slots;
 }
