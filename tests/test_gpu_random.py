@@ -139,3 +139,24 @@ def test_random_kv(seed):
     assert gst == ab.OK and gtotal == need and intact
     np.testing.assert_array_equal(got_table, want_table)
     np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_inplace_merge(seed):
+    from test_gpu_merge import check_merge, instances
+
+    rng = np.random.default_rng(9000 + seed)
+    m, k = int(rng.choice([2, 3, 4, 8])), int(rng.choice([1, 2]))
+    heads = m * k * int(rng.integers(1, 3))
+    d = int(rng.choice([1, 4, 8, 32, 64]))
+    eb = int(rng.choice([1, 2, 2, 4]))
+    B = int(rng.choice([1, 4, 16]))
+    S = int(rng.integers(1, 12))
+    lens = [rng.integers(0, 5 * B + 1, size=S).tolist() for _ in range(m)]
+    worst = max(sum((x + B - 1) // B for x in row) for row in lens)
+    P = worst + int(rng.integers(0, 12))
+    W = max(1, max((x + B - 1) // B for row in lens for x in row)) + int(rng.integers(0, 2))
+    cfg, insts = instances(m, k, lens, n_heads=heads, d=d, B=B, layers=int(rng.integers(1, 4)),
+                           P=max(P, 1), W=W, seed=seed + 1, elem_bytes=eb)
+    hint = {ab.TUNE_KV_BLOCKS_HINT: m * worst} if seed % 2 else None
+    check_merge(cfg, insts, m, k, int(rng.integers(0, k * m)), tune=hint)
