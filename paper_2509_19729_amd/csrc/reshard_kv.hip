@@ -253,8 +253,11 @@ __device__ __forceinline__ uint32_t block_vec(uint32_t h, uint32_t c, uint32_t t
   return ((c * B + t) * heads + h) * dv + x;
 }
 
-template <int SL, int DL, bool NT>
-__global__ void __launch_bounds__(kThreads)
+// THREADS lanes per workgroup, ITERS vectors per lane: the tile has at most THREADS * ITERS
+// vectors.  All global loads of a tile are issued before the first LDS write and all LDS
+// reads before the first global store, so a lane has ITERS accesses in flight on each side.
+template <int SL, int DL, bool NT, int THREADS, int ITERS>
+__global__ void __launch_bounds__(THREADS)
 kv_regroup_staged_kernel(const KVArgs a, const KVStagedGeom g, const int32_t* __restrict__ ws) {
   extern __shared__ u32x4 tile_lds[];  // [tile_tokens][tile_heads][dv]
   const uint32_t tid = threadIdx.x;
@@ -275,31 +278,48 @@ kv_regroup_staged_kernel(const KVArgs a, const KVStagedGeom g, const int32_t* __
     const uint64_t soff = uint64_t(layer) * a.src_layer_stride + uint64_t(sb) * a.src_block_bytes;
     char* dp = a.dst + uint64_t(layer) * a.dst_layer_stride + uint64_t(b) * a.dst_block_bytes;
 
-    for (uint32_t v = tid; v < g.tile_vecs; v += kThreads) {  // source order -> LDS
+    u32x4 val[ITERS];
+    uint32_t slot[ITERS];  // index in LDS; ~0u: nothing to move
+#pragma unroll
+    for (int u = 0; u < ITERS; ++u) {  // source order -> registers
+      const uint32_t v = u * THREADS + tid;
       const uint32_t e = fd_div(v, a.dv), x = v - e * dv;
       uint32_t t, h;
       staged_split<SL>(e, g, t, h);
       const uint32_t hp = h0 + h;
-      if (hp < a.heads_dst.d && sb >= 0) {
+      slot[u] = ~0u;
+      if (v < g.tile_vecs && hp < a.heads_dst.d && sb >= 0) {
         const uint32_t hg = a.head0 + hp;
         const uint32_t s = fd_div(hg, a.heads_src);
         const uint32_t hs = hg - s * a.heads_src.d;
         const char* pool = (a.n_src <= 2) ? ((s == a.rank_lo) ? a.src_lo : a.src_hi) : a.src[s];
         const uint32_t sv = block_vec<SL>(hs, c, t0 + t, x, a.heads_src.d, B, dv);
-        tile_lds[(t * g.tile_heads + h) * dv + x] = ld<NT, u32x4>(pool + soff + uint64_t(sv) * 16);
+        val[u] = ld<NT, u32x4>(pool + soff + uint64_t(sv) * 16);
+        slot[u] = (t * g.tile_heads + h) * dv + x;
       }
     }
+#pragma unroll
+    for (int u = 0; u < ITERS; ++u)
+      if (slot[u] != ~0u) tile_lds[slot[u]] = val[u];
     __syncthreads();
-    for (uint32_t v = tid; v < g.tile_vecs; v += kThreads) {  // LDS -> destination order
+    uint32_t dvi[ITERS];
+#pragma unroll
+    for (int u = 0; u < ITERS; ++u) {  // LDS -> registers, destination order
+      const uint32_t v = u * THREADS + tid;
       const uint32_t e = fd_div(v, a.dv), x = v - e * dv;
       uint32_t t, h;
       staged_split<DL>(e, g, t, h);
       const uint32_t hp = h0 + h;
-      if (hp < a.heads_dst.d && sb >= 0) {
-        const uint32_t dvi = block_vec<DL>(hp, c, t0 + t, x, a.heads_dst.d, B, dv);
-        st<NT, u32x4>(dp + uint64_t(dvi) * 16, tile_lds[(t * g.tile_heads + h) * dv + x]);
+      slot[u] = ~0u;
+      if (v < g.tile_vecs && hp < a.heads_dst.d && sb >= 0) {
+        slot[u] = (t * g.tile_heads + h) * dv + x;
+        dvi[u] = block_vec<DL>(hp, c, t0 + t, x, a.heads_dst.d, B, dv);
+        val[u] = tile_lds[slot[u]];
       }
     }
+#pragma unroll
+    for (int u = 0; u < ITERS; ++u)
+      if (slot[u] != ~0u) st<NT, u32x4>(dp + uint64_t(dvi[u]) * 16, val[u]);
     __syncthreads();  // the next tile reuses the LDS buffer
   }
 }
@@ -472,12 +492,28 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
   const bool want_staged =
       p->tune.kv_staged == 1 || (p->tune.kv_staged == 0 && head_vec_bytes < 128);
   if (convert && vec == 16 && want_staged && head_vec_bytes <= 4096) {
-    const uint32_t target = 4096u * uint32_t(unroll == 1 ? 2 : unroll);  // tile bytes aimed at
-    uint32_t tt = std::max<uint32_t>(1, 1024u / uint32_t(head_vec_bytes));
-    tt = std::min(tt, B);
-    while (B % tt) --tt;  // tokens per tile divide the block
-    uint32_t th = std::max<uint32_t>(1, target / (tt * uint32_t(head_vec_bytes)));
-    th = std::min<uint32_t>(th, uint32_t(p->heads_dst));
+    // Tile: 1 KiB runs on the destination's side first (scattered writes cost more than
+    // scattered reads), then as much of the other axis as the lanes' vectors allow.
+    // Measured best: 256 lanes x 2 vectors (8 KiB); 4 vectors per lane lose 3-8 %.
+    const int st_threads = p->tune.kv_threads == 64 ? 64 : 256;
+    int st_iters = p->tune.kv_unroll;
+    if (st_iters != 1 && st_iters != 2 && st_iters != 4) st_iters = 2;
+    while (uint32_t(st_threads * st_iters) < dv) st_iters *= 2;  // dv <= 256 = 64 * 4
+    const uint32_t cap = uint32_t(st_threads * st_iters);  // vectors of a tile at most
+    const uint32_t run = std::max<uint32_t>(1, 1024u / uint32_t(head_vec_bytes));
+    uint32_t tt, th;
+    if (s.kv_layout_dst == AMOEBA_KV_HEAD_MAJOR) {
+      // the destination's contiguous runs are tokens of a head: 1 KiB of them first
+      tt = std::min(run, B);
+      while (B % tt || tt * dv > cap) --tt;  // tokens per tile divide the block; dv <= cap
+      th = std::min<uint32_t>(std::max<uint32_t>(1, cap / (tt * dv)), uint32_t(p->heads_dst));
+    } else {
+      // the destination's contiguous runs are heads of a token
+      th = std::min<uint32_t>(run, uint32_t(p->heads_dst));
+      while (th * dv > cap) --th;
+      tt = std::min<uint32_t>(std::max<uint32_t>(1, cap / (th * dv)), B);
+      while (B % tt) --tt;
+    }
     KVStagedGeom g;
     g.tile_tokens = tt;
     g.tile_heads = th;
@@ -494,15 +530,38 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
       return AMOEBA_ERR_INVALID_ARG;
     }
     const size_t lds = size_t(g.tile_vecs) * 16;
-#define AMOEBA_STAGED(SL, DL, NTV)                                                        \
-  hipLaunchKernelGGL((kv_regroup_staged_kernel<SL, DL, NTV>), grid, dim3(kThreads), lds,  \
-                     stream, a, g, a.ws)
-    if (s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR) {
-      if (nt) AMOEBA_STAGED(AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR, true);
-      else AMOEBA_STAGED(AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR, false);
+    const bool src_hm = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR;
+#define AMOEBA_STAGED(T, I)                                                                       \
+  do {                                                                                            \
+    if (src_hm && nt)                                                                             \
+      hipLaunchKernelGGL((kv_regroup_staged_kernel<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR,   \
+                                                   true, T, I>),                                  \
+                         grid, dim3(T), lds, stream, a, g, a.ws);                                 \
+    else if (src_hm)                                                                              \
+      hipLaunchKernelGGL((kv_regroup_staged_kernel<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR,   \
+                                                   false, T, I>),                                 \
+                         grid, dim3(T), lds, stream, a, g, a.ws);                                 \
+    else if (nt)                                                                                  \
+      hipLaunchKernelGGL((kv_regroup_staged_kernel<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR,   \
+                                                   true, T, I>),                                  \
+                         grid, dim3(T), lds, stream, a, g, a.ws);                                 \
+    else                                                                                          \
+      hipLaunchKernelGGL((kv_regroup_staged_kernel<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR,   \
+                                                   false, T, I>),                                 \
+                         grid, dim3(T), lds, stream, a, g, a.ws);                                 \
+  } while (0)
+    if (st_threads == 64) {
+      switch (st_iters) {
+        case 1: AMOEBA_STAGED(64, 1); break;
+        case 2: AMOEBA_STAGED(64, 2); break;
+        default: AMOEBA_STAGED(64, 4); break;
+      }
     } else {
-      if (nt) AMOEBA_STAGED(AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR, true);
-      else AMOEBA_STAGED(AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR, false);
+      switch (st_iters) {
+        case 1: AMOEBA_STAGED(256, 1); break;
+        case 2: AMOEBA_STAGED(256, 2); break;
+        default: AMOEBA_STAGED(256, 4); break;
+      }
     }
 #undef AMOEBA_STAGED
     if (!hip_ok("kv staged regroup kernel launch failed", err)) return AMOEBA_ERR_HIP;
