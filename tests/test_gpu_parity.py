@@ -243,6 +243,22 @@ def test_kv_layout_conversion_staged_and_direct(staged, n_heads, d, B, k, kp, rp
                  tune={ab.TUNE_KV_STAGED: staged, ab.TUNE_KV_GRID: 5, ab.TUNE_KV_UNROLL: 4})
 
 
+@pytest.mark.parametrize("threads,unroll", [(64, 1), (64, 2), (64, 4), (256, 1), (256, 2),
+                                            (256, 4)])
+def test_kv_staged_kernel_launch_shapes(threads, unroll):
+    """Every workgroup size and vectors-per-lane count of the LDS-staged kernel, from 16-byte
+    head vectors to 2 KiB ones (128 vectors: more than 64 lanes x 1 hold, so the library
+    raises the count itself), ragged head groups and a block of 12 tokens."""
+    tune = {ab.TUNE_KV_STAGED: 1, ab.TUNE_KV_THREADS: threads, ab.TUNE_KV_UNROLL: unroll}
+    for n_heads, d, B, k, kp, rp in [(10, 32, 16, 2, 1, 0), (6, 8, 12, 3, 1, 0),
+                                     (4, 1024, 4, 2, 1, 0), (12, 128, 16, 2, 3, 1)]:
+        for lay_s, lay_d in [(TM, HM), (HM, TM)]:
+            cfg, pools, table, lens = kv_case(k, [40, 100, 7, 33, 0, 16], lay_s, lay_d,
+                                              n_heads=n_heads, d=d, B=B, layers=2,
+                                              seed=threads + unroll + d)
+            check_kv(cfg, k, kp, rp, pools, table, lens, tune=tune)
+
+
 @pytest.mark.parametrize("hint", [1, 37, 10_000])
 def test_kv_blocks_in_use_hint_only_changes_the_launch_shape(hint):
     """The hint bounds the grid; too small a hint makes workgroups stride, too large leaves
