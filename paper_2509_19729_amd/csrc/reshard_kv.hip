@@ -156,8 +156,13 @@ kv_regroup_kernel(const KVArgs a, const int32_t* __restrict__ ws) {
   const uint32_t total = (uint32_t)ws[kWsTotal];
   const int32_t* __restrict__ worklist = ws + kWsHeader + a.num_seqs;
   const uint32_t n_items = total * a.tiles_per_block.d;  // < 2^32, bounded on the host
+  // multi-wavefront workgroups take their items in the XCD-chunked order
+  constexpr bool kChunked = THREADS > 64;
+  const uint32_t n_loop = kChunked ? xcd_loop_bound(n_items) : n_items;
 
-  for (uint32_t w = blockIdx.x; w < n_items; w += gridDim.x) {
+  for (uint32_t wi = blockIdx.x; wi < n_loop; wi += gridDim.x) {
+    const uint32_t w = kChunked ? xcd_item(wi, n_items) : wi;
+    if (kChunked && w >= n_items) continue;
     const uint32_t b = fd_div(w, a.tiles_per_block);
     const uint32_t tile = w - b * a.tiles_per_block.d;
     const int32_t sb = worklist[b];  // -1: the source id was out of range, block is skipped
@@ -266,8 +271,12 @@ kv_regroup_staged_kernel(const KVArgs a, const KVStagedGeom g, const int32_t* __
   const int32_t* __restrict__ worklist = ws + kWsHeader + a.num_seqs;
   const uint32_t n_items = total * a.tiles_per_block.d;
   const uint32_t dv = a.dv.d, B = g.block_tokens;
+  constexpr bool kChunked = THREADS > 64;  // see xcd_item()
+  const uint32_t n_loop = kChunked ? xcd_loop_bound(n_items) : n_items;
 
-  for (uint32_t w = blockIdx.x; w < n_items; w += gridDim.x) {
+  for (uint32_t wi = blockIdx.x; wi < n_loop; wi += gridDim.x) {
+    const uint32_t w = kChunked ? xcd_item(wi, n_items) : wi;
+    if (kChunked && w >= n_items) continue;  // uniform over the workgroup: no barrier is skipped by part of it
     const uint32_t b = fd_div(w, a.tiles_per_block);
     const uint32_t tile = w - b * a.tiles_per_block.d;
     const int32_t sb = worklist[b];
@@ -419,10 +428,11 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
   if (vec != 16 || (unroll != 2 && unroll != 4)) unroll = 1;
   if (vec != 16) threads = 256;
   else if (threads != 256 && threads != 64)
-    // One wavefront per 1 KiB tile is fastest when the grid is tight (6.45 vs 6.25 TB/s),
-    // but with the grid sized by the pool's capacity every idle workgroup costs dispatch
-    // time; 4 KiB tiles cut that cost by four.  So: small tiles when the caller bounded the
-    // blocks in use, large ones otherwise.
+    // One wavefront per 1 KiB tile is fastest when the grid is tight (6.45 TB/s against 6.4
+    // for four wavefronts in the XCD-chunked order, 6.15 in plain order), but with the grid
+    // sized by the pool's capacity every idle workgroup costs dispatch time; 4 KiB tiles cut
+    // that cost by four.  So: small tiles when the caller bounded the blocks in use, large
+    // ones otherwise.
     threads = p->tune.kv_blocks_hint > 0 ? 64 : 256;
   const bool nt = p->tune.nontemporal != 2;
 
