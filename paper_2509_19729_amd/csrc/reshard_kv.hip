@@ -495,12 +495,14 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
   };
   dim3 grid;
 
-  // Converting between the layouts goes through LDS when one head vector is shorter than
-  // a cache line (see kv_regroup_staged_kernel); with 256-byte head vectors the direct
-  // gather already moves whole lines and measured the same or faster.
+  // Converting between the layouts goes through LDS when one head vector is at most one
+  // 128-byte cache line (see kv_regroup_staged_kernel): below a line the direct gather
+  // fetches every line twice (4.0 against 6.3 TB/s), at exactly one line it moves whole
+  // lines but in single-line pieces (6.0 against 6.3).  With 256-byte head vectors the
+  // direct gather measured the same or faster.
   const bool convert = s.kv_layout_src != s.kv_layout_dst;
   const bool want_staged =
-      p->tune.kv_staged == 1 || (p->tune.kv_staged == 0 && head_vec_bytes < 128);
+      p->tune.kv_staged == 1 || (p->tune.kv_staged == 0 && head_vec_bytes <= 128);
   if (convert && vec == 16 && want_staged && head_vec_bytes <= 4096) {
     // Tile: 1 KiB runs on the destination's side first (scattered writes cost more than
     // scattered reads), then as much of the other axis as the lanes' vectors allow.
