@@ -230,12 +230,18 @@ def main():
                      "launches_per_step": len(kv_calls),
                      "avg_launch_ms": round(kv_ms / len(kv_calls), 4)},
     }
+    if w_gbps is not None and w_ms > kv_ms:
+        # the weight kernel is the dominant one of this workload (few, short sequences)
+        out["roofline"].update({"kernel": "reshard_weights_kernel", "achieved": round(w_gbps, 1),
+                                "frac": round(w_gbps / PEAK_HBM_GBPS, 4),
+                                "alg_bytes_per_launch": w_alg, "launches_per_step": 1,
+                                "avg_launch_ms": round(w_ms, 4)})
     # HBM bytes per launch from the committed rocprofv3 counter summary of this workload
     # (FETCH_SIZE + WRITE_SIZE, each calibrated on the plain copy kernel), if there is one
     summary = os.path.join(ROOT, "profiles", f"reshard_{w.name}_{args.layout}.txt")
     if os.path.exists(summary) and not args.tune:
         for line in open(summary):
-            if line.startswith("traffic_bytes_per_launch kv_regroup_kernel:"):
+            if line.startswith(f"traffic_bytes_per_launch {out['roofline']['kernel']}:"):
                 out["roofline"]["traffic"] = int(line.split(":")[1])
 
     if args.graph:
