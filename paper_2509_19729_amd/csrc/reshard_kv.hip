@@ -156,13 +156,14 @@ kv_regroup_kernel(const KVArgs a, const int32_t* __restrict__ ws) {
   const uint32_t total = (uint32_t)ws[kWsTotal];
   const int32_t* __restrict__ worklist = ws + kWsHeader + a.num_seqs;
   const uint32_t n_items = total * a.tiles_per_block.d;  // < 2^32, bounded on the host
-  // multi-wavefront workgroups take their items in the XCD-chunked order
-  constexpr bool kChunked = THREADS > 64;
-  const uint32_t n_loop = kChunked ? xcd_loop_bound(n_items) : n_items;
+  // Items are taken in the XCD-chunked order (see xcd_item()): +4 % for workgroups of four
+  // wavefronts, +1-2 % for single-wavefront ones on the block gather (a plain copy with
+  // single-wavefront workgroups does not gain from it).
+  const uint32_t n_loop = xcd_loop_bound(n_items);
 
   for (uint32_t wi = blockIdx.x; wi < n_loop; wi += gridDim.x) {
-    const uint32_t w = kChunked ? xcd_item(wi, n_items) : wi;
-    if (kChunked && w >= n_items) continue;
+    const uint32_t w = xcd_item(wi, n_items);
+    if (w >= n_items) continue;
     const uint32_t b = fd_div(w, a.tiles_per_block);
     const uint32_t tile = w - b * a.tiles_per_block.d;
     const int32_t sb = worklist[b];  // -1: the source id was out of range, block is skipped
@@ -271,12 +272,11 @@ kv_regroup_staged_kernel(const KVArgs a, const KVStagedGeom g, const int32_t* __
   const int32_t* __restrict__ worklist = ws + kWsHeader + a.num_seqs;
   const uint32_t n_items = total * a.tiles_per_block.d;
   const uint32_t dv = a.dv.d, B = g.block_tokens;
-  constexpr bool kChunked = THREADS > 64;  // see xcd_item()
-  const uint32_t n_loop = kChunked ? xcd_loop_bound(n_items) : n_items;
+  const uint32_t n_loop = xcd_loop_bound(n_items);  // XCD-chunked order, see xcd_item()
 
   for (uint32_t wi = blockIdx.x; wi < n_loop; wi += gridDim.x) {
-    const uint32_t w = kChunked ? xcd_item(wi, n_items) : wi;
-    if (kChunked && w >= n_items) continue;  // uniform over the workgroup: no barrier is skipped by part of it
+    const uint32_t w = xcd_item(wi, n_items);
+    if (w >= n_items) continue;  // uniform over the workgroup: no barrier is skipped by part of it
     const uint32_t b = fd_div(w, a.tiles_per_block);
     const uint32_t tile = w - b * a.tiles_per_block.d;
     const int32_t sb = worklist[b];
