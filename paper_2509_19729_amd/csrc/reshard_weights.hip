@@ -15,8 +15,9 @@
 // is the smallest one: one 16-byte vector per lane and one workgroup per tile,
 // leaving the overlap of reads and writes to the many short-lived wavefronts in
 // flight (larger tiles or persistent grid-stride loops cost 5-15 %).  Tiles are numbered in
-// destination order (layer, segment, position) so that the workgroups in flight
-// at any time sweep one contiguous window of the destination.  Within a strided
+// destination order (layer, segment, position) and each of the 8 XCDs takes its own
+// contiguous eighth of them, so that the workgroups in flight at any time sweep eight
+// contiguous windows of the destination, one per XCD and L2.  Within a strided
 // rectangle the lane's vector index n is split into (row, column) with a
 // multiply-high division by the row length.
 #include <algorithm>
@@ -56,7 +57,12 @@ __global__ void __launch_bounds__(THREADS) reshard_weights_kernel(const WArgs a)
   constexpr uint32_t kTileVecs = THREADS * UNROLL;
   const uint32_t tid = threadIdx.x;
 
-  for (uint32_t w = blockIdx.x; w < a.total_tiles; w += gridDim.x) {
+  // Tiles are taken in the XCD-chunked order (see xcd_item()): every XCD sweeps its own
+  // contiguous eighth of the (layer, tile) space; measured +2-3 % over the plain order here.
+  const uint32_t n_loop = xcd_loop_bound(a.total_tiles);
+  for (uint32_t wi = blockIdx.x; wi < n_loop; wi += gridDim.x) {
+    const uint32_t w = xcd_item(wi, a.total_tiles);
+    if (w >= a.total_tiles) continue;
     const uint32_t layer = fd_div(w, a.tiles_per_layer);
     const uint32_t t = w - layer * a.tiles_per_layer.d;
     // last segment whose first tile is <= t (uniform across the workgroup)
