@@ -17,3 +17,12 @@ def pytest_configure(config):
 def _oracle_built():
     import oracle
     oracle.build()
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _library_built():
+    """The tests load the library that is built; only when there is none do they build it
+    (the product itself never builds or falls back: binding.lib() raises)."""
+    from paper_2509_19729_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
