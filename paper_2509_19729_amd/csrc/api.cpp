@@ -322,7 +322,10 @@ int amoeba_plan_tune(amoeba_plan_t* plan, int knob, int value) {
     case AMOEBA_TUNE_NONTEMPORAL: plan->tune.nontemporal = value; break;
     case AMOEBA_TUNE_KV_STAGED: plan->tune.kv_staged = value; break;
     case AMOEBA_TUNE_KV_BLOCKS_HINT: plan->tune.kv_blocks_hint = value; break;
-    case AMOEBA_TUNE_W_PART: plan->tune.w_part = value; break;
+    case AMOEBA_TUNE_W_PART:
+      if (value > 2) { set_error("amoeba_plan_tune: AMOEBA_TUNE_W_PART takes 0, 1 or 2"); return AMOEBA_ERR_INVALID_ARG; }
+      plan->tune.w_part = value;
+      break;
     default: set_error("amoeba_plan_tune: unknown knob"); return AMOEBA_ERR_INVALID_ARG;
   }
   return AMOEBA_OK;

@@ -170,6 +170,16 @@ def test_reshard_calls_reject_null_arguments_without_a_gpu():
     L.amoeba_plan_destroy(None)
 
 
+def test_tune_rejects_unknown_knobs_and_bad_values():
+    plan = ab.amoeba_plan(ab.ModelShape(2, 24, 8, 4, 4, 72), 1, 2, 0)
+    for knob in range(10):
+        ab.amoeba_plan_tune(plan, knob, 0)           # 0 restores the built-in choice
+    for knob, value in [(10, 1), (-1, 1), (ab.TUNE_W_PART, 3), (ab.TUNE_KV_GRID, -5)]:
+        with pytest.raises(ab.AmoebaError):
+            ab.amoeba_plan_tune(plan, knob, value)
+    assert "AMOEBA_TUNE_W_PART" in ab.amoeba_last_error() or "bad plan or value" in ab.amoeba_last_error()
+
+
 def test_workload_recipes_are_seeded_and_well_formed():
     for name in wl.ORDER:
         w = wl.WORKLOADS[name]
