@@ -7,6 +7,7 @@
 #include <cstddef>
 #include <cstdint>
 #include <cstring>
+#include <vector>
 
 namespace {
 
@@ -229,6 +230,11 @@ int merge_kv_inplace_t(const ao_kv* c, int k, int m, int rp, void* local_v,
 
   E* local = static_cast<E*>(local_v);
   bool bad_id = false;
+  // remote_blocks_out counts the slots of the reshaped pool that receive remote heads: one
+  // per distinct new id.  An id outside the pool has no slot and is not counted; a block two
+  // sequences of one instance share is one slot, filled (twice, with the same bytes) and
+  // counted once.  It is the number the bytes moved follow from: count x sub-block x layers.
+  std::vector<char> filled((size_t)(P * m), 0);
   int64_t copied = 0;
   for (int64_t g2 = 0; g2 < m; ++g2) {
     const E* remote = static_cast<const E*>(remote_v[g2]);
@@ -240,7 +246,7 @@ int merge_kv_inplace_t(const ao_kv* c, int k, int m, int rp, void* local_v,
         const int64_t id = b * m + g2;                 // reshaped id, same on every rank
         dst_table[(g2 * S + i) * W + j] = (int32_t)id;
         if (g2 == g) continue;                         // local heads stay where they are
-        ++copied;
+        if (!filled[(size_t)id]) { filled[(size_t)id] = 1; ++copied; }
         for (int64_t l = 0; l < c->kv_layers; ++l) {
           const E* from = remote + (l * P + b) * old_block + g * sub;  // heads of r' in block b
           E* to = local + (l * P * m + id) * sub;

@@ -114,7 +114,9 @@ int ao_reshard_kv(const ao_kv* c, int src_tp, int dst_tp, int dst_rank,
  * instance-major order and is the same for every target rank.  remote_pools[g] is
  * ignored.  A negative length or a row that is too short gives AO_ERR_OVERFLOW
  * (nothing written, table all -1); an id outside [0, P) gives a -1 entry, skips the
- * block and returns AO_ERR_BLOCK_ID.  remote_blocks_out: blocks copied per layer. */
+ * block and returns AO_ERR_BLOCK_ID.  remote_blocks_out: the slots (distinct new ids) of
+ * the reshaped pool that received remote heads, per layer: a skipped id has no slot and is
+ * not counted, a block id two sequences of one instance share is one slot, counted once. */
 int ao_merge_kv_inplace(const ao_kv* c, int src_tp, int m, int dst_rank, void* local_pool,
                         const void* const* remote_pools, const int32_t* const* src_tables,
                         const int32_t* const* seq_lens, int32_t* dst_table,

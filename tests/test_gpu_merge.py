@@ -124,6 +124,22 @@ def test_merge_degenerate_and_error_cases():
     check_merge(cfg, insts, 2, 1, 0, expect=oracle.ERR_BLOCK_ID)
 
 
+def test_merge_shared_block_ids_and_a_bad_id_count_slots_once():
+    """Two sequences of one instance share a block (a common prefix) and another cell holds
+    an id outside the pool: the table carries the shared id twice, the slot is filled and
+    counted once, the bad cell reads -1 and is not counted (the oracle's count is pinned on
+    the CPU from the input tables alone)."""
+    cfg, insts = instances(3, 1, [[13, 8, 9], [5, 22, 6], [16, 2, 7]], n_heads=6, d=8, B=4,
+                           layers=2, P=24, W=8, seed=21)
+    insts[1]["table"][2, 0] = insts[1]["table"][0, 0]
+    insts[1]["table"][2, 1] = insts[1]["table"][0, 1]
+    for rp in range(3):
+        check_merge(cfg, insts, 3, 1, rp)
+    insts[2]["table"][0, 1] = 24 + 3
+    for rp in range(3):
+        check_merge(cfg, insts, 3, 1, rp, expect=oracle.ERR_BLOCK_ID)
+
+
 def test_merge_rejects_plans_that_do_not_qualify():
     kv = oracle.KV(kv_layers=1, n_kv_heads=8, head_dim=8, block_tokens=4, num_seqs=2,
                    max_blocks_per_seq=4, src_pool_blocks=8, dst_pool_blocks=16)

@@ -182,3 +182,69 @@ def test_errors():
     assert oracle.merge_kv_inplace(cfg, k, m, 0, local, [None, None], tabs, lens)[0] == oracle.ERR_ARG
     assert oracle.merge_kv_inplace(cfg, k, 3, 0, local, [None, insts[1]["pools"][0], None],
                                    tabs + [tabs[0]], lens + [lens[0]])[0] == oracle.ERR_ARG
+
+
+def _remote_slots(tables, lens, g, m, P, B):
+    """Slots of worker g's reshaped pool that receive remote heads, straight from the inputs:
+    the distinct (block id, instance) pairs over the remote instances' in-range table cells."""
+    slots = set()
+    for g2 in range(m):
+        if g2 == g:
+            continue
+        nb = (np.asarray(lens[g2], dtype=np.int64) + B - 1) // B
+        for i, n in enumerate(nb):
+            for b in tables[g2][i, :n]:
+                if 0 <= b < P:
+                    slots.add((int(b), g2))
+    return slots
+
+
+def test_remote_block_count_is_the_number_of_slots_filled():
+    """The count reported next to the merge is the number of distinct slots of the reshaped
+    pool that receive remote heads (Sec. 3.1, in-place migration: one slot per old block and
+    instance): an id outside the pool has no slot, and a block two sequences of one instance
+    share (a common prefix) is one slot.  Expected values come from the input tables alone,
+    and from the bytes that actually changed in the pool."""
+    m, k = 3, 1
+    lens = [[13, 8, 9], [5, 22, 6], [16, 2, 7]]
+    cfg, insts = make_instances(m, k, lens, n_heads=6, seed=11)
+    P, B, S = cfg.src_pool_blocks, cfg.block_tokens, cfg.num_seqs
+    tabs = [i["table"].copy() for i in insts]
+    lns = [i["lens"] for i in insts]
+    # instance 1: sequences 0 and 2 share their first block; instance 2: one id out of range
+    tabs[1][2, 0] = tabs[1][0, 0]
+    tabs[2][0, 1] = P + 3
+    sub = cfg.n_kv_heads // m * 2 * B * cfg.head_dim
+    for g in range(m):
+        local = insts[g]["pools"][0].copy()
+        remote = [None if g2 == g else insts[g2]["pools"][0] for g2 in range(m)]
+        st, table, n = oracle.merge_kv_inplace(cfg, k, m, g, local, remote, tabs, lns)
+        slots = _remote_slots(tabs, lns, g, m, P, B)
+        assert st == oracle.ERR_BLOCK_ID
+        assert n == len(slots)
+        # fewer than the table cells of the remote instances: the shared block and, for the
+        # workers that see instance 2 as remote, the bad id
+        cells = sum(int(((np.asarray(lns[g2], dtype=np.int64) + B - 1) // B).sum())
+                    for g2 in range(m) if g2 != g)
+        assert n == cells - (1 if g != 1 else 0) - (1 if g != 2 else 0)
+        # the bytes that changed lie inside exactly those slots (random payloads: a filled
+        # slot differs from what was there)
+        before = insts[g]["pools"][0].reshape(cfg.kv_layers, P * m, sub)
+        after = local.reshape(cfg.kv_layers, P * m, sub)
+        changed = {int(x) for x in np.nonzero((before != after).any(axis=(0, 2)))[0]}
+        assert changed == {b * m + g2 for b, g2 in slots}
+        # the shared block appears twice in the table with one id; the bad cell reads -1
+        assert table[1 * S + 2, 0] == table[1 * S + 0, 0] == tabs[1][0, 0] * m + 1
+        assert table[2 * S + 0, 1] == -1
+
+
+def test_remote_block_count_on_a_clean_table_is_the_remote_cell_count():
+    m, k = 4, 2
+    lens = [[13, 1, 8, 0], [5, 22, 3, 9], [16, 2, 7, 7], [1, 1, 30, 4]]
+    cfg, insts = make_instances(m, k, lens, n_heads=16, seed=4)
+    B = cfg.block_tokens
+    res = merge_all_ranks(cfg, insts, m, k)
+    for r, (_, _, n) in res.items():
+        g = r % m
+        assert n == sum(int(((insts[g2]["lens"].astype(np.int64) + B - 1) // B).sum())
+                        for g2 in range(m) if g2 != g)
