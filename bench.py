@@ -30,7 +30,15 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="llama7b")
+    ap.add_argument("--workload", default="all",
+                    help="all (default): the four 7B-and-larger configurations in one run, the "
+                         "headline being the largest (llama13b); or one of tiny, llama7b, "
+                         "llama13b, gqa70b, long8b, qwen3moe")
+    ap.add_argument("--placement", default="workload", choices=["workload", "sorted"],
+                    help="sorted: diagnostic, the workload's source block ids in ascending order")
+    ap.add_argument("--no-bound", action="store_true",
+                    help="reshard mode: leave amoeba_model_shape.kv_blocks_bound at 0 in the "
+                         "timed plan (the run reports both rates either way)")
     ap.add_argument("--layout", default="hm-hm", choices=["hm-hm", "tm-tm", "tm-hm", "hm-tm"])
     ap.add_argument("--kv-layers", type=int, default=0,
                     help="KV layers resident per call (0 = all that fit the workload definition)")
@@ -53,9 +61,11 @@ def parse():
                          "overlap: n layers per step resharded on a side stream while a synthetic "
                          "inference step runs on the main stream")
     ap.add_argument("--instances", type=int, default=4, help="m for --mode merge-inplace")
-    ap.add_argument("--no-hint", action="store_true",
-                    help="merge-inplace: do not tell the library how many blocks are in use")
     return ap.parse_args()
+
+
+HEADLINE = "llama13b"                                     # the largest single-GPU configuration
+DEFAULT_SET = ["llama7b", "gqa70b", "long8b", "llama13b"]  # every 7B-and-larger configuration
 
 
 def main():
@@ -66,11 +76,7 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
-
-    from paper_2509_19729_amd import binding as ab
-    from paper_2509_19729_amd import workloads as wl
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -84,7 +90,66 @@ def main():
         return weights_padded(args)
     if args.mode == "overlap":
         return overlap(args)
-    w = wl.WORKLOADS[args.workload]
+
+    if args.workload != "all":
+        out = reshard(args, args.workload, cpu_budget_s=0 if args.no_cpu_baseline else 12.0)
+        print(json.dumps(out), flush=True)
+        return
+    # Default: every 7B-and-larger configuration in one run.  The headline fields are those of
+    # the largest one; `configs` carries the others, each timed the same way (W warm-ups, K
+    # timed steps) on its own pools, which are freed before the next one is built.
+    rows = []
+    head = None
+    for name in DEFAULT_SET:
+        is_head = name == HEADLINE
+        budget = 0 if args.no_cpu_baseline else (15.0 if is_head else 4.0)
+        out = reshard(args, name, cpu_budget_s=budget)
+        print(f"bench.py: {name}: {out['value']} GB/s, {out['ms_per_step']} ms/step",
+              file=sys.stderr, flush=True)
+        if is_head:
+            head = out
+        rows.append(summary_row(name, out))
+    head["configs"] = rows
+    print(json.dumps(head), flush=True)
+
+
+def summary_row(name, out):
+    c, r = out["config"], out["roofline"]
+    row = {"workload": name, "gbps": out["value"], "pct_of_hbm_peak": out["pct_of_hbm_peak"],
+           "ms_per_tp_transform": out["ms_per_step"], "alg_bytes": c["weights_alg_bytes"] + c["kv_alg_bytes"],
+           "weights_ms": c["weights_ms"], "weights_gbps": c["weights_gbps"], "kv_ms": c["kv_ms"],
+           "kv_gbps": c["kv_gbps"], "kv_gbps_without_bound": c["kv_gbps_without_bound"],
+           "dominant_kernel": r["kernel"], "frac": r["frac"], "avg_launch_ms": r["avg_launch_ms"],
+           "plain_copy_gbps": c["plain_copy_gbps"], "tune": c["tune"]}
+    if "cpu_baseline" in out:
+        row["oracle_gbps"] = out["cpu_baseline"]["value"]
+        row["oracle_sample"] = out["cpu_baseline"]["sample"]
+    return row
+
+
+def kernel_sources_digest():
+    """SHA-256 over the library's sources: a profile summary under profiles/ records the
+    digest of the build it was taken on, and its traffic figure is only quoted for that build."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2509_19729_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h", ".cpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def reshard(args, workload, cpu_budget_s):
+    """One configuration: W warm-up steps, K timed steps, the side measurements (outside the
+    timed region), the oracle sample.  Returns the JSON object."""
+    import numpy as np
+    import torch
+
+    from paper_2509_19729_amd import binding as ab
+    from paper_2509_19729_amd import workloads as wl
+
+    w = wl.WORKLOADS[workload]
     if args.head_dim or args.kv_heads:
         heads = args.kv_heads or w.n_kv_heads
         w = w.scaled(head_dim=args.head_dim or w.head_dim, n_kv_heads=heads, n_q_heads=heads,
@@ -94,25 +159,37 @@ def main():
 
     lens = wl.seq_lens(w)
     table, src_pool_blocks = wl.block_placement(w, lens)
+    if args.placement == "sorted":
+        # diagnostic: the same set of source ids, ascending along the new block order, so that
+        # the reads sweep the source pools monotonically like the writes sweep the target
+        used = table >= 0
+        table = table.copy()
+        table[used] = np.sort(table[used])
     total_blocks = int(wl.blocks_per_seq(lens, w.block_tokens).sum())
     dst_pool_blocks = total_blocks + 64
     kv_layers = args.kv_layers or w.n_layers
     if w.name == "llama13b" and not args.kv_layers:
         kv_layers = 16  # the full 40-layer cache (src + dst, about 494 GB) exceeds the 288 GB of HBM
-    shape = ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim,
-                          elem_bytes=w.elem_bytes, kv_block_tokens=w.block_tokens,
-                          kv_layout_src=lay_s, kv_layout_dst=lay_d, kv_layers=kv_layers,
-                          num_seqs=w.num_seqs, max_blocks_per_seq=table.shape[1],
-                          src_pool_blocks=src_pool_blocks, dst_pool_blocks=dst_pool_blocks,
-                          n_experts=w.n_experts)
-    plan = ab.amoeba_plan(shape, w.src_tp, w.dst_tp, w.dst_rank)
-    # the scheduler that owns the block tables knows how many blocks are in use; the library
-    # only sees device-side lengths and would otherwise size its grid by the pool's capacity
-    ab.amoeba_plan_tune(plan, ab.TUNE_KV_BLOCKS_HINT, total_blocks)
     knobs = {n[len("TUNE_"):].lower(): getattr(ab, n) for n in dir(ab) if n.startswith("TUNE_")}
-    for kv in filter(None, args.tune.split(",")):
-        name, val = kv.split("=")
-        ab.amoeba_plan_tune(plan, knobs[name], int(val))
+
+    def make_plan(layers, bound):
+        # the scheduler that owns the block tables knows how many blocks are in use and says so
+        # in the shape; the library only sees device-side lengths and would otherwise size its
+        # grid by the pool's capacity
+        shape = ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim,
+                              w.ffn_dim, elem_bytes=w.elem_bytes, kv_block_tokens=w.block_tokens,
+                              kv_layout_src=lay_s, kv_layout_dst=lay_d, kv_layers=layers,
+                              num_seqs=w.num_seqs, max_blocks_per_seq=table.shape[1],
+                              src_pool_blocks=src_pool_blocks, dst_pool_blocks=dst_pool_blocks,
+                              n_experts=w.n_experts, kv_blocks_bound=bound)
+        p = ab.amoeba_plan(shape, w.src_tp, w.dst_tp, w.dst_rank)
+        for kv in filter(None, args.tune.split(",")):
+            name, val = kv.split("=")
+            ab.amoeba_plan_tune(p, knobs[name], int(val))
+        return p
+
+    bound = 0 if args.no_bound else total_blocks
+    plan = make_plan(kv_layers, bound)
 
     # ---- synthetic state, generated on the device (values ~ N(0, 0.02), 16-bit) ----
     gen = torch.Generator(device="cuda")
@@ -141,26 +218,27 @@ def main():
     # When the whole cache does not fit beside its target (13B: 40 layers), the model's layers
     # are covered by several calls over the resident pools: full chunks of kv_layers and one
     # shorter call for the remainder, so that a step still moves every layer's worth of bytes.
-    kv_calls = [plan] * (w.n_layers // kv_layers)
-    if w.n_layers % kv_layers:
-        rest = ab.amoeba_plan(ab.ModelShape(**{**shape.__dict__, "kv_layers": w.n_layers % kv_layers}),
-                              w.src_tp, w.dst_tp, w.dst_rank)
-        ab.amoeba_plan_tune(rest, ab.TUNE_KV_BLOCKS_HINT, total_blocks)
-        for kv in filter(None, args.tune.split(",")):
-            name, val = kv.split("=")
-            ab.amoeba_plan_tune(rest, knobs[name], int(val))
-        kv_calls.append(rest)
+    def calls_for(b):
+        first = plan if b == bound else make_plan(kv_layers, b)
+        calls = [first] * (w.n_layers // kv_layers)
+        if w.n_layers % kv_layers:
+            calls.append(make_plan(w.n_layers % kv_layers, b))
+        return calls
 
+    kv_calls = calls_for(bound)
     w_alg = 2 * dst_bytes
     kv_alg = 2 * total_blocks * bb_d * w.n_layers
     alg_bytes = w_alg + kv_alg
+
+    def kv_step(calls):
+        for p in calls:
+            ab.amoeba_reshard_kv(p, kv_src, table_d, lens_d, kv_dst, out_table)
 
     def step(ev=None):
         ab.amoeba_reshard_weights(plan, w_src, w_dst)
         if ev is not None:
             ev[0].record()
-        for p in kv_calls:
-            ab.amoeba_reshard_kv(p, kv_src, table_d, lens_d, kv_dst, out_table)
+        kv_step(kv_calls)
         if ev is not None:
             ev[1].record()
 
@@ -188,9 +266,26 @@ def main():
     w_ms = dev_ms - kv_ms
     value = alg_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # plain streaming copy of the same access shape (one wavefront per 1 KiB tile, one 16-byte
-    # vector per lane, non-temporal): the rate this GPU reaches on a copy,
-    # and a transfer of known size for calibrating traffic counters (outside the timed region)
+    def timed_kv(calls, reps=5):
+        for _ in range(2):
+            kv_step(calls)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            kv_step(calls)
+        b.record()
+        torch.cuda.synchronize()
+        return kv_alg * reps / (a.elapsed_time(b) * 1e-3) / 1e9
+
+    # outside the timed region: the KV calls without the bound on the blocks in use (the grid
+    # then covers the pool's capacity, four wavefronts per workgroup) ...
+    other = calls_for(0 if bound else total_blocks)
+    kv_other_gbps = timed_kv(other)
+    for p in set(other):
+        p.close()
+    # ... and a plain streaming copy of the same access shape (one wavefront per 1 KiB tile, one
+    # 16-byte vector per lane, non-temporal): the rate this GPU reaches on a copy, and a
+    # transfer of known size for calibrating traffic counters
     copy_src = next(t for t in w_src if t is not None)
     copy_bytes = min(copy_src.numel(), w_dst.numel()) * 2 // 16 * 16
     for _ in range(2):
@@ -205,6 +300,10 @@ def main():
 
     kv_gbps = kv_alg / (kv_ms * 1e-3) / 1e9
     w_gbps = w_alg / (w_ms * 1e-3) / 1e9 if w_ms > 0 else None
+    kgx, kgy, klanes, _ = ab.amoeba_plan_launch_shape(plan, ab.KERNEL_KV_REGROUP, 16)
+    tune = (f"kv_blocks_bound={bound} in the shape" if bound else "no kv_blocks_bound") + \
+        f" -> KV grid {kgx} x {kgy} workgroups of {klanes} lanes" + \
+        (f"; overrides: {args.tune}" if args.tune else "")
     out = {
         "metric": "reshard throughput (read+write) of one TP transform, one target rank",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -218,10 +317,14 @@ def main():
                                f"{w.num_seqs} seqs / {int(lens.sum())} tokens / {total_blocks} "
                                f"blocks of {w.block_tokens}, KV layers resident {kv_layers} "
                                f"({len(kv_calls)} KV call(s) per step cover {w.n_layers} layers)",
-                   "kv_layout": args.layout, "weights_alg_bytes": w_alg, "kv_alg_bytes": kv_alg,
+                   "kv_layout": args.layout, "placement": args.placement,
+                   "weights_alg_bytes": w_alg, "kv_alg_bytes": kv_alg,
                    "weights_ms": round(w_ms, 4), "weights_gbps": w_gbps and round(w_gbps, 1),
                    "kv_ms": round(kv_ms, 4), "kv_ms_median": round(kv_each[len(kv_each) // 2], 4),
-                   "kv_ms_min": round(kv_each[0], 4), "tune": args.tune,
+                   "kv_ms_min": round(kv_each[0], 4), "kv_gbps": round(kv_gbps, 1),
+                   "kv_gbps_without_bound": round(kv_other_gbps if bound else kv_gbps, 1),
+                   "kv_gbps_with_bound": round(kv_gbps if bound else kv_other_gbps, 1),
+                   "tune": tune,
                    "plain_copy_gbps": round(copy_gbps, 1), "plain_copy_bytes": copy_bytes},
         "roofline": {"bound": "hbm", "kernel": "kv_regroup_kernel", "achieved": round(kv_gbps, 1),
                      "peak": PEAK_HBM_GBPS, "unit": "GB/s",
@@ -236,13 +339,21 @@ def main():
                                 "frac": round(w_gbps / PEAK_HBM_GBPS, 4),
                                 "alg_bytes_per_launch": w_alg, "launches_per_step": 1,
                                 "avg_launch_ms": round(w_ms, 4)})
-    # HBM bytes per launch from the committed rocprofv3 counter summary of this workload
-    # (FETCH_SIZE + WRITE_SIZE, each calibrated on the plain copy kernel), if there is one
+    # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, each calibrated on the plain copy kernel)
+    # cannot be counted inside this process; they come from the committed rocprofv3 summary of
+    # this workload, and only if that summary was taken on this build of the kernels
     summary = os.path.join(ROOT, "profiles", f"reshard_{w.name}_{args.layout}.txt")
-    if os.path.exists(summary) and not args.tune:
-        for line in open(summary):
-            if line.startswith(f"traffic_bytes_per_launch {out['roofline']['kernel']}:"):
-                out["roofline"]["traffic"] = int(line.split(":")[1])
+    if os.path.exists(summary) and not args.tune and args.placement == "workload" and bound:
+        text = open(summary).read()
+        if f"kernel_sources_digest {kernel_sources_digest()}" in text:
+            for line in text.splitlines():
+                if line.startswith(f"traffic_bytes_per_launch {out['roofline']['kernel']}:"):
+                    out["roofline"]["traffic"] = int(line.split(":")[1])
+                    out["roofline"]["traffic_source"] = os.path.relpath(summary, ROOT)
+        else:
+            out["roofline"]["traffic_source"] = (
+                f"{os.path.relpath(summary, ROOT)} was taken on another build of the kernels; "
+                "not quoted")
 
     if args.graph:
         # the reshard calls only enqueue kernels (no allocation, no memset node), so a step can
@@ -262,14 +373,17 @@ def main():
         rc, n_blocks = ab.amoeba_kv_status(plan)
         assert rc == ab.OK and n_blocks == total_blocks, (rc, n_blocks)
 
-    if not args.no_cpu_baseline:
+    for p in set(kv_calls) | {plan}:
+        p.close()
+    del w_src, w_dst, kv_src, kv_dst
+    torch.cuda.empty_cache()
+    if cpu_budget_s:
         out["cpu_baseline"] = cpu_baseline(w, lens, table, src_pool_blocks, dst_pool_blocks,
-                                           lay_s, lay_d)
+                                           lay_s, lay_d, cpu_budget_s)
         # the sample's rate applied to the whole transform (an extrapolation, not a measurement)
         out["cpu_baseline"]["extrapolated_ms_per_tp_transform"] = round(
             alg_bytes / (out["cpu_baseline"]["value"] * 1e9) * 1e3, 1)
-    plan.close()
-    print(json.dumps(out), flush=True)
+    return out
 
 
 def weights_padded(args):
@@ -283,7 +397,7 @@ def weights_padded(args):
     from paper_2509_19729_amd import binding as ab
     from paper_2509_19729_amd import workloads as wl
 
-    w = wl.WORKLOADS[args.workload]
+    w = wl.WORKLOADS["llama7b" if args.workload == "all" else args.workload]
     T, page = 4, 2 << 20
 
     def shape(sp, dp):
@@ -297,14 +411,14 @@ def weights_padded(args):
             return ab.amoeba_plan_expert_info(plan, side)[1]
         return ab.amoeba_plan_padded_info(plan, side)[1]
 
-    def timed(plan, src, dst):
+    def timed(plan, src, dst, part=ab.PART_ALL):
         for _ in range(args.warmup):
-            ab.amoeba_reshard_weights(plan, src, dst)
+            ab.amoeba_reshard_weights_part(plan, src, dst, part)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
         for _ in range(args.steps):
-            ab.amoeba_reshard_weights(plan, src, dst)
+            ab.amoeba_reshard_weights_part(plan, src, dst, part)
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / args.steps
@@ -326,10 +440,9 @@ def weights_padded(args):
     rank, off, nbytes, src_layer = ab.amoeba_plan_ffn_view(p_pad)
     attn = ffn_start(p_pad, 1)
     # the FFN partitions stay where they are; only q/k/v/o are re-sliced (into a fresh buffer)
-    ab.amoeba_plan_tune(p_pad, ab.TUNE_W_PART, 1)
     a_src = [buf(ab.amoeba_plan_shard_bytes(p_pad, 0))]
     a_dst = buf(ab.amoeba_plan_shard_bytes(p_pad, 1))
-    ms_attn = timed(p_pad, a_src, a_dst)
+    ms_attn = timed(p_pad, a_src, a_dst, ab.PART_ATTENTION)
     res["scale_up_padded"] = {"ms": round(ms_attn, 4), "bytes_copied": attn * w.n_layers,
                               "ffn_bytes_kept_in_place": nbytes * w.n_layers,
                               "ffn_bytes_released": (src_layer - nbytes - ffn_start(p_pad, 0))
@@ -377,7 +490,7 @@ def overlap(args):
     from paper_2509_19729_amd import binding as ab
     from paper_2509_19729_amd import workloads as wl
 
-    w = wl.WORKLOADS[args.workload]
+    w = wl.WORKLOADS["llama7b" if args.workload == "all" else args.workload]
     lens = wl.seq_lens(w)
     table, src_pool = wl.block_placement(w, lens)
     total = int(wl.blocks_per_seq(lens, w.block_tokens).sum())
@@ -388,9 +501,9 @@ def overlap(args):
         shape = ab.ModelShape(n, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim,
                               elem_bytes=2, kv_block_tokens=w.block_tokens, kv_layers=n,
                               num_seqs=w.num_seqs, max_blocks_per_seq=table.shape[1],
-                              src_pool_blocks=src_pool, dst_pool_blocks=dst_pool)
+                              src_pool_blocks=src_pool, dst_pool_blocks=dst_pool,
+                              kv_blocks_bound=total)
         p = ab.amoeba_plan(shape, w.src_tp, w.dst_tp, w.dst_rank)
-        ab.amoeba_plan_tune(p, ab.TUNE_KV_BLOCKS_HINT, total)
         knobs = {k[len("TUNE_"):].lower(): getattr(ab, k) for k in dir(ab) if k.startswith("TUNE_")}
         for kv in filter(None, args.tune.split(",")):
             name, val = kv.split("=")
@@ -508,7 +621,7 @@ def merge_naive(args):
     from paper_2509_19729_amd import binding as ab
     from paper_2509_19729_amd import workloads as wl
 
-    w = wl.WORKLOADS[args.workload]
+    w = wl.WORKLOADS["llama7b" if args.workload == "all" else args.workload]
     m, rank = args.instances, 1 % args.instances
     per, nb, tables, S, P, W = _instances(w, m)
     L = args.kv_layers or w.n_layers
@@ -521,9 +634,8 @@ def merge_naive(args):
                               w.ffn_dim, elem_bytes=2, kv_block_tokens=w.block_tokens,
                               kv_layout_src=ab.KV_TOKEN_MAJOR, kv_layout_dst=ab.KV_TOKEN_MAJOR,
                               kv_layers=L, num_seqs=S, max_blocks_per_seq=W, src_pool_blocks=P,
-                              dst_pool_blocks=need)
+                              dst_pool_blocks=need, kv_blocks_bound=need)
         plan = ab.amoeba_plan(shape, 1, m, rank)
-        ab.amoeba_plan_tune(plan, ab.TUNE_KV_BLOCKS_HINT, need)
         plans.append(plan)
         bs, bd = ab.amoeba_plan_kv_block_bytes(plan, 0), ab.amoeba_plan_kv_block_bytes(plan, 1)
         t = torch.empty(L * P * bs // 2, dtype=torch.bfloat16, device="cuda")
@@ -583,20 +695,19 @@ def merge_inplace(args):
     from paper_2509_19729_amd import binding as ab
     from paper_2509_19729_amd import workloads as wl
 
-    w = wl.WORKLOADS[args.workload]
+    w = wl.WORKLOADS["llama7b" if args.workload == "all" else args.workload]
     m, rank = args.instances, 1 % args.instances
     per, nb, tables, S, P, W = _instances(w, m)
     L = args.kv_layers or w.n_layers
-    shape = ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim,
-                          elem_bytes=2, kv_block_tokens=w.block_tokens, kv_layers=L, num_seqs=S,
-                          max_blocks_per_seq=W, src_pool_blocks=P, dst_pool_blocks=P * m)
-    plan = ab.amoeba_plan(shape, 1, m, rank)
-    assert ab.amoeba_plan_merge_factor(plan) == m
     # the scheduler that owns the tables knows how many blocks are remote; the library sizes
     # its grid by this bound instead of by the pool's capacity
     n_remote_host = sum(int(x.sum()) for g, x in enumerate(nb) if g != rank)
-    if not args.no_hint:
-        ab.amoeba_plan_tune(plan, ab.TUNE_KV_BLOCKS_HINT, n_remote_host)
+    shape = ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim,
+                          elem_bytes=2, kv_block_tokens=w.block_tokens, kv_layers=L, num_seqs=S,
+                          max_blocks_per_seq=W, src_pool_blocks=P, dst_pool_blocks=P * m,
+                          kv_blocks_bound=0 if args.no_bound else n_remote_host)
+    plan = ab.amoeba_plan(shape, 1, m, rank)
+    assert ab.amoeba_plan_merge_factor(plan) == m
     bb = ab.amoeba_plan_kv_block_bytes(plan, 0)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(0xA30EBA10 + w.index)
@@ -654,9 +765,9 @@ def merge_inplace(args):
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(w, lens, table, src_pool_blocks, dst_pool_blocks, lay_s, lay_d):
+def cpu_baseline(w, lens, table, src_pool_blocks, dst_pool_blocks, lay_s, lay_d, budget_s=12.0):
     """The oracle, single thread, on a bounded sample of the same workload: a few real-shape
-    layers of weights and one layer of the whole KV table, repeated until about 12 s of CPU
+    layers of weights and one layer of the whole KV table, repeated until about budget_s of CPU
     time have been spent (host speeds differ by an order of magnitude between boxes)."""
     import numpy as np
 
@@ -682,7 +793,7 @@ def cpu_baseline(w, lens, table, src_pool_blocks, dst_pool_blocks, lay_s, lay_d)
     t_w = t_kv = 0.0
     bytes_w = bytes_kv = 0
     reps = 0
-    budget_s, max_reps = 12.0, 64
+    max_reps = 64
     while reps < max_reps and t_w + t_kv < budget_s:
         t0 = time.perf_counter()
         if moe:

@@ -9,10 +9,10 @@
  *             re-sliced by attention head and by FFN column/row partition
  *             (paper Sec. 2.2; Sec. 3.2, Eq. (1) and the definition of U', D').
  *   KV cache: every paged block is regrouped by KV head under a compacted,
- *             rewritten block table (paper Sec. 3.1: the head-range rule "worker
- *             W_i keeps heads (H/TP)(i-1)+1 .. (H/TP)i", the page-friendly
- *             token-first block and the header-centric block
- *             [Block, Header, K/V, Token]).
+ *             rewritten block table (paper Sec. 3.1: each worker of a TP group owns
+ *             one contiguous run of H/TP heads, in rank order; the token-first
+ *             block layout of the base solution and the header-centric layout
+ *             of Improvement 1).
  *
  * Everything is an opaque move of 1-, 2- or 4-byte elements: no arithmetic on
  * the payload.  All compute runs in HIP kernels; there is no CPU fallback.
@@ -36,10 +36,19 @@
  * Block tables are int32 [num_seqs][max_blocks_per_seq], padded with -1.  One
  * source table serves all source ranks (one instance, one scheduler).
  *
- * Threading: a plan is immutable after amoeba_plan() except for its small
- * device workspace, which amoeba_reshard_kv() uses: two amoeba_reshard_kv()
- * calls on the same plan must not overlap in time.  amoeba_reshard_weights()
- * calls may overlap freely.
+ * Device memory and threading.  The host side of a plan is immutable after
+ * amoeba_plan().  The plan owns two device workspaces, allocated once by
+ * amoeba_plan() and freed by amoeba_plan_destroy(); the reshard calls themselves
+ * never allocate, free or synchronise:
+ *   - for amoeba_reshard_kv(): 4 * (8 + num_seqs + dst_pool_blocks) bytes (a status
+ *     header, the scanned base of every sequence, and the source id of every new
+ *     block, which the block-regroup kernel reads instead of searching the table);
+ *   - for amoeba_merge_kv_inplace(), when the plan qualifies: about
+ *     8 * m * src_pool_blocks bytes (a flag and a work-list entry per new block id).
+ * The kernels of a call write these, so two amoeba_reshard_kv() calls (or two
+ * amoeba_merge_kv_inplace() calls) on the same plan must not overlap in time; use
+ * one plan per stream.  amoeba_reshard_weights() uses no workspace and its calls
+ * may overlap freely.
  */
 #ifndef AMOEBA_H
 #define AMOEBA_H
@@ -85,26 +94,8 @@ enum {
   AMOEBA_T_GATE = 4, AMOEBA_T_UP = 5, AMOEBA_T_DOWN = 6, AMOEBA_T_COUNT = 7
 };
 
-/* Knobs for amoeba_plan_tune(); 0 restores the built-in choice. */
-enum {
-  AMOEBA_TUNE_W_GRID = 0,      /* workgroups of the weight kernel (0: one per tile)          */
-  AMOEBA_TUNE_W_UNROLL = 1,    /* 16-byte vectors per lane per tile: 1, 2, 4 or 8            */
-  AMOEBA_TUNE_W_THREADS = 2,   /* lanes per workgroup: 64, 128 or 256                        */
-  AMOEBA_TUNE_KV_GRID = 3,     /* workgroups per layer of the KV regroup kernel              */
-  AMOEBA_TUNE_KV_UNROLL = 4,   /* vectors per lane per tile: 1, 2 or 4                       */
-  AMOEBA_TUNE_KV_THREADS = 5,  /* lanes per workgroup: 64 or 256                             */
-  AMOEBA_TUNE_NONTEMPORAL = 6, /* 1: streaming (nt) loads/stores, 2: plain                   */
-  AMOEBA_TUNE_KV_STAGED = 7,   /* 1: LDS-staged layout-converting regroup, 2: direct         */
-  AMOEBA_TUNE_KV_BLOCKS_HINT = 8, /* upper bound on the blocks the next KV calls will move (the
-                                  host scheduler knows it; the library only sees device-side
-                                  lengths).  Sizes the grid: without it the grid covers the
-                                  pool's capacity and idle workgroups cost dispatch time when
-                                  the pool is far from full.  A hint that is too small is
-                                  still correct (workgroups stride), only slower.            */
-  AMOEBA_TUNE_W_PART = 9       /* amoeba_reshard_weights moves 0: everything, 1: only q/k/v/o
-                                  (for a padded scale-up whose FFN part is a zero-copy view,
-                                  see amoeba_plan_ffn_view), 2: only the FFN tensors        */
-};
+/* Which tensors amoeba_reshard_weights_part() moves. */
+enum { AMOEBA_PART_ALL = 0, AMOEBA_PART_ATTENTION = 1, AMOEBA_PART_FFN = 2 };
 
 /* Caller-owned POD; amoeba_plan() copies it. */
 typedef struct {
@@ -122,6 +113,13 @@ typedef struct {
   int32_t pad_max_tp;      /* T: finest TP degree of the model's TP set; src_tp, dst_tp | T */
   int32_t n_experts;       /* 0: dense FFN; E > 0: mixture of experts, see below           */
   int64_t pad_page_bytes;  /* allocation granule the partitions are aligned to (2 MiB)    */
+  /* Upper bound on the KV blocks in use (sum over sequences of ceil(len / kv_block_tokens)),
+   * as the scheduler that owns the block tables knows it when it asks for the transform;
+   * 0 = unknown.  The lengths themselves are device data, so without the bound the regroup
+   * grid has to cover dst_pool_blocks and the workgroups past the blocks in use cost
+   * dispatch time (up to 30 % with a pool far from full).  A bound that turns out too
+   * small is still correct: the workgroups stride over the rest, only slower. */
+  int64_t kv_blocks_bound;
 } amoeba_model_shape;
 
 /*
@@ -149,17 +147,18 @@ typedef struct amoeba_plan_s amoeba_plan_t;
  * Host-side planning (Sec. 3.2: partition boundaries are fixed per model and TP
  * set, so they are computed once).  Builds the per-layer table of strided copy
  * segments for the weights and the stride description of both KV layouts (the
- * role of the paper's kv_stride_order(), Sec. 3.1), and allocates a device
- * workspace of 4*(num_seqs + dst_pool_blocks + 8) bytes on the current device
- * for the KV path (skipped, without error, when no GPU is present; then
- * amoeba_reshard_kv() fails with AMOEBA_ERR_HIP).
+ * role of the paper's kv_stride_order(), Sec. 3.1), and allocates the device
+ * workspaces described at the top of this file on the current device (skipped,
+ * without error, when no GPU is present; then amoeba_reshard_kv() fails with
+ * AMOEBA_ERR_HIP).
  * Returns NULL and sets amoeba_last_error() if: a size is not positive (num_seqs,
  * max_blocks_per_seq and the pool sizes may be 0), dst_rank is outside
  * [0, dst_tp), either TP degree exceeds AMOEBA_MAX_TP or does not divide
  * n_q_heads, n_kv_heads and ffn_dim (n_experts instead of ffn_dim for a
  * mixture-of-experts model; fewer KV heads than ranks, i.e. head
  * replication, is unsupported), n_q_heads is not a multiple of n_kv_heads,
- * a layout or elem_bytes is unknown, or a pool has more than 2^31-1 blocks.
+ * a layout or elem_bytes is unknown, a pool has more than 2^31-1 blocks, or
+ * kv_blocks_bound is negative.
  */
 amoeba_plan_t* amoeba_plan(const amoeba_model_shape* shape, int src_tp, int dst_tp, int dst_rank);
 
@@ -179,6 +178,15 @@ void amoeba_plan_destroy(amoeba_plan_t* plan);
  */
 int amoeba_reshard_weights(const amoeba_plan_t* plan, const void* const* src_shards, void* dst,
                            void* stream);
+
+/* The same with a choice of tensors: AMOEBA_PART_ALL (what amoeba_reshard_weights() does),
+ * AMOEBA_PART_ATTENTION (q, k, v, o and, in a padded layout, the zero gap behind them) or
+ * AMOEBA_PART_FFN (gate, up, down or the experts).  For the scale-up of Sec. 3.2,
+ * Improvement 1: when amoeba_plan_ffn_view() says the target's FFN partitions are a page
+ * range of a source buffer that is kept in place, only the attention part is re-sliced.
+ * Bytes of `dst` outside the chosen part are not touched. */
+int amoeba_reshard_weights_part(const amoeba_plan_t* plan, const void* const* src_shards,
+                                void* dst, int part, void* stream);
 
 /*
  * KV cache (Sec. 3.1): scan sequence lengths, rewrite the block table, regroup
@@ -290,19 +298,6 @@ int amoeba_plan_kv_stride_order(const amoeba_plan_t* plan, int side, int64_t out
  * src_rank = -1 marks a zero fill (a gap of a padded destination). */
 int amoeba_plan_num_segments(const amoeba_plan_t* plan);
 int amoeba_plan_segment(const amoeba_plan_t* plan, int index, int64_t out[7]);
-
-/* Launch-shape knobs (AMOEBA_TUNE_*), for measurement sweeps.  Not thread-safe
- * against concurrent reshard calls on the same plan. */
-int amoeba_plan_tune(amoeba_plan_t* plan, int knob, int value);
-
-/* Measurement aid, not part of the reshard: a plain device-to-device streaming copy
- * with the same access shape as the reshard kernels (16 B per lane, `threads` lanes per
- * workgroup: 64 or 256; `unroll` loads in flight per lane: 1, 2, 4 or 8; `grid` workgroups,
- * 0 = one per tile; nontemporal as in AMOEBA_TUNE_NONTEMPORAL).  Gives the copy rate this GPU reaches and a transfer of
- * known size to calibrate HBM traffic counters.  dst, src: DEVICE pointers, 16-byte
- * aligned, non-overlapping; bytes a multiple of 16. */
-int amoeba_copy_baseline(void* dst, const void* src, size_t bytes, int threads, int unroll,
-                         int grid, int nontemporal, void* stream);
 
 /* Text of the calling thread's last error ("" if none). */
 const char* amoeba_last_error(void);

@@ -23,21 +23,27 @@ OK, ERR_INVALID_ARG, ERR_HIP, ERR_OVERFLOW, ERR_BLOCK_ID = 0, 1, 2, 3, 4
 
 T_Q, T_K, T_V, T_O, T_GATE, T_UP, T_DOWN = range(7)
 
+PART_ALL, PART_ATTENTION, PART_FFN = 0, 1, 2
+
+# include/amoeba_measure.h
 TUNE_W_GRID, TUNE_W_UNROLL, TUNE_W_THREADS, TUNE_KV_GRID, TUNE_KV_UNROLL, TUNE_KV_THREADS, \
-    TUNE_NONTEMPORAL, TUNE_KV_STAGED, TUNE_KV_BLOCKS_HINT, TUNE_W_PART = range(10)
+    TUNE_NONTEMPORAL, TUNE_KV_STAGED, TUNE_KV_BLOCKS_HINT, TUNE_KV_SMALL_TABLE = range(10)
+KERNEL_WEIGHTS, KERNEL_KV_REGROUP, KERNEL_MERGE_COPY = 0, 1, 2
 
 MAX_TP = 16
 
 # every symbol include/amoeba.h declares
 EXPORTS = [
-    "amoeba_plan", "amoeba_plan_destroy", "amoeba_reshard_weights", "amoeba_reshard_kv",
-    "amoeba_kv_status", "amoeba_plan_shard_bytes", "amoeba_plan_kv_block_bytes",
-    "amoeba_plan_src_rank_mask", "amoeba_plan_kv_rank_mask", "amoeba_plan_tensor_info",
-    "amoeba_plan_kv_stride_order", "amoeba_plan_num_segments", "amoeba_plan_segment",
-    "amoeba_plan_tune", "amoeba_copy_baseline", "amoeba_last_error",
-    "amoeba_merge_kv_inplace", "amoeba_merge_kv_status", "amoeba_plan_merge_factor",
-    "amoeba_plan_padded_info", "amoeba_plan_ffn_view", "amoeba_plan_expert_info",
+    "amoeba_plan", "amoeba_plan_destroy", "amoeba_reshard_weights", "amoeba_reshard_weights_part",
+    "amoeba_reshard_kv", "amoeba_kv_status", "amoeba_plan_shard_bytes",
+    "amoeba_plan_kv_block_bytes", "amoeba_plan_src_rank_mask", "amoeba_plan_kv_rank_mask",
+    "amoeba_plan_tensor_info", "amoeba_plan_kv_stride_order", "amoeba_plan_num_segments",
+    "amoeba_plan_segment", "amoeba_last_error", "amoeba_merge_kv_inplace",
+    "amoeba_merge_kv_status", "amoeba_plan_merge_factor", "amoeba_plan_padded_info",
+    "amoeba_plan_ffn_view", "amoeba_plan_expert_info",
 ]
+# every symbol include/amoeba_measure.h declares
+MEASURE_EXPORTS = ["amoeba_plan_tune", "amoeba_plan_launch_shape", "amoeba_copy_baseline"]
 
 
 class _Shape(ctypes.Structure):
@@ -48,7 +54,7 @@ class _Shape(ctypes.Structure):
                [("src_pool_blocks", ctypes.c_int64), ("dst_pool_blocks", ctypes.c_int64),
                 ("w_layout_src", ctypes.c_int32), ("w_layout_dst", ctypes.c_int32),
                 ("pad_max_tp", ctypes.c_int32), ("n_experts", ctypes.c_int32),
-                ("pad_page_bytes", ctypes.c_int64)]
+                ("pad_page_bytes", ctypes.c_int64), ("kv_blocks_bound", ctypes.c_int64)]
 
 
 @dataclass
@@ -74,6 +80,7 @@ class ModelShape:
     pad_max_tp: int = 0
     n_experts: int = 0
     pad_page_bytes: int = 0
+    kv_blocks_bound: int = 0
 
     def _c(self) -> _Shape:
         return _Shape(*[getattr(self, f.name) for f in fields(self)])
@@ -100,6 +107,8 @@ def lib() -> ctypes.CDLL:
     L.amoeba_plan_destroy.argtypes = [vp]
     L.amoeba_reshard_weights.restype = i32
     L.amoeba_reshard_weights.argtypes = [vp, ctypes.POINTER(vp), vp, vp]
+    L.amoeba_reshard_weights_part.restype = i32
+    L.amoeba_reshard_weights_part.argtypes = [vp, ctypes.POINTER(vp), vp, i32, vp]
     L.amoeba_reshard_kv.restype = i32
     L.amoeba_reshard_kv.argtypes = [vp, ctypes.POINTER(vp), vp, vp, vp, vp, vp]
     L.amoeba_kv_status.restype = i32
@@ -122,6 +131,8 @@ def lib() -> ctypes.CDLL:
     L.amoeba_plan_segment.argtypes = [vp, i32, ctypes.POINTER(i64)]
     L.amoeba_plan_tune.restype = i32
     L.amoeba_plan_tune.argtypes = [vp, i32, i32]
+    L.amoeba_plan_launch_shape.restype = i32
+    L.amoeba_plan_launch_shape.argtypes = [vp, i32, i32, ctypes.POINTER(i64)]
     L.amoeba_copy_baseline.restype = i32
     L.amoeba_copy_baseline.argtypes = [vp, vp, ctypes.c_size_t, i32, i32, i32, i32, vp]
     L.amoeba_merge_kv_inplace.restype = i32
@@ -218,6 +229,15 @@ def amoeba_reshard_weights(plan: Plan, src_shards, dst, stream=None, check: bool
     return rc
 
 
+def amoeba_reshard_weights_part(plan: Plan, src_shards, dst, part: int, stream=None,
+                                check: bool = True) -> int:
+    rc = lib().amoeba_reshard_weights_part(plan.handle, _ptr_array(src_shards, plan.src_tp),
+                                           _ptr(dst), part, _stream_handle(stream))
+    if check and rc != OK:
+        raise AmoebaError(rc, amoeba_last_error())
+    return rc
+
+
 def amoeba_reshard_kv(plan: Plan, src_blocks, src_block_tables, seq_lens, dst_blocks,
                       dst_block_tables, stream=None, check: bool = True) -> int:
     rc = lib().amoeba_reshard_kv(plan.handle, _ptr_array(src_blocks, plan.src_tp),
@@ -286,6 +306,15 @@ def amoeba_plan_tune(plan: Plan, knob: int, value: int) -> None:
     rc = lib().amoeba_plan_tune(plan.handle, knob, value)
     if rc != OK:
         raise AmoebaError(rc, amoeba_last_error())
+
+
+def amoeba_plan_launch_shape(plan: Plan, kernel: int, align_bytes: int = 16):
+    """(grid.x, grid.y, lanes per workgroup, work items per grid.y slice)"""
+    out = (ctypes.c_int64 * 4)()
+    rc = lib().amoeba_plan_launch_shape(plan.handle, kernel, align_bytes, out)
+    if rc != OK:
+        raise AmoebaError(rc, amoeba_last_error())
+    return tuple(int(x) for x in out)
 
 
 def amoeba_copy_baseline(dst, src, nbytes: int, threads: int = 64, unroll: int = 1, grid: int = 0,

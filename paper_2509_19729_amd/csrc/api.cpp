@@ -7,6 +7,7 @@
 #include <string>
 
 #include "../../include/amoeba.h"
+#include "../../include/amoeba_measure.h"
 #include "launch.h"
 #include "plan.h"
 
@@ -67,6 +68,7 @@ amoeba_plan_t* amoeba_plan(const amoeba_model_shape* shape, int src_tp, int dst_
   p->device = -1;
   p->n_cu = 0;
   p->workspace = nullptr;
+  p->status_ws = nullptr;
   p->merge_workspace = nullptr;
   p->merge_workspace_bytes = 0;
   p->workspace_bytes = 0;
@@ -121,17 +123,26 @@ void amoeba_plan_destroy(amoeba_plan_t* plan) {
   delete plan;
 }
 
-int amoeba_reshard_weights(const amoeba_plan_t* plan, const void* const* src_shards, void* dst,
-                           void* stream) {
+int amoeba_reshard_weights_part(const amoeba_plan_t* plan, const void* const* src_shards,
+                                void* dst, int part, void* stream) {
   if (!plan || !src_shards || !dst) {
     set_error("amoeba_reshard_weights: NULL plan, src_shards or dst");
     return AMOEBA_ERR_INVALID_ARG;
   }
+  if (part != AMOEBA_PART_ALL && part != AMOEBA_PART_ATTENTION && part != AMOEBA_PART_FFN) {
+    set_error("amoeba_reshard_weights_part: part must be AMOEBA_PART_ALL, _ATTENTION or _FFN");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
   std::string err;
-  const int rc = amoeba::launch_reshard_weights(plan, src_shards, dst,
+  const int rc = amoeba::launch_reshard_weights(plan, src_shards, dst, part,
                                                 static_cast<hipStream_t>(stream), &err);
   if (rc != AMOEBA_OK) set_error("amoeba_reshard_weights: " + err);
   return rc;
+}
+
+int amoeba_reshard_weights(const amoeba_plan_t* plan, const void* const* src_shards, void* dst,
+                           void* stream) {
+  return amoeba_reshard_weights_part(plan, src_shards, dst, AMOEBA_PART_ALL, stream);
 }
 
 int amoeba_reshard_kv(const amoeba_plan_t* plan, const void* const* src_blocks,
@@ -141,20 +152,31 @@ int amoeba_reshard_kv(const amoeba_plan_t* plan, const void* const* src_blocks,
     set_error("amoeba_reshard_kv: NULL plan or src_blocks");
     return AMOEBA_ERR_INVALID_ARG;
   }
+  if (!plan->workspace) {
+    set_error("amoeba_reshard_kv: the plan has no device workspace (it was created without a GPU)");
+    return AMOEBA_ERR_HIP;
+  }
+  int current_device = -1;
+  if (hipGetDevice(&current_device) != hipSuccess || current_device != plan->device) {
+    set_error("amoeba_reshard_kv: the current device is not the one the plan's workspace was "
+              "allocated on");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
   std::string err;
-  const int rc =
-      amoeba::launch_reshard_kv(plan, src_blocks, src_block_tables, seq_lens, dst_blocks,
-                                dst_block_tables, static_cast<hipStream_t>(stream), &err);
+  const int rc = amoeba::launch_reshard_kv(plan, plan->workspace, src_blocks, src_block_tables,
+                                           seq_lens, dst_blocks, dst_block_tables,
+                                           static_cast<hipStream_t>(stream), &err);
   if (rc != AMOEBA_OK) set_error("amoeba_reshard_kv: " + err);
+  else plan->status_ws = plan->workspace;
   return rc;
 }
 
 int amoeba_kv_status(const amoeba_plan_t* plan, void* stream, int64_t* total_blocks) {
-  if (!plan || !plan->workspace) {
-    set_error("amoeba_kv_status: NULL plan or no device workspace");
+  if (!plan || !plan->status_ws) {
+    set_error("amoeba_kv_status: NULL plan, or no KV reshard was enqueued on it");
     return AMOEBA_ERR_INVALID_ARG;
   }
-  return read_status("amoeba_kv_status", plan->workspace, stream, total_blocks);
+  return read_status("amoeba_kv_status", plan->status_ws, stream, total_blocks);
 }
 
 int amoeba_merge_kv_inplace(const amoeba_plan_t* plan, void* local_pool,
@@ -310,6 +332,29 @@ int amoeba_copy_baseline(void* dst, const void* src, size_t bytes, int threads, 
   return rc;
 }
 
+int amoeba_plan_launch_shape(const amoeba_plan_t* plan, int kernel, int align_bytes,
+                             int64_t out[4]) {
+  if (!plan || !out || align_bytes < 1 || (align_bytes & (align_bytes - 1))) {
+    set_error("amoeba_plan_launch_shape: bad plan or out, or align_bytes is not a power of two");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  amoeba::LaunchShape L;
+  std::string err;
+  bool ok = false;
+  switch (kernel) {
+    case 0: ok = amoeba::weights_launch_geometry(plan, align_bytes, &L, &err); break;
+    case 1: ok = amoeba::kv_launch_geometry(plan, align_bytes, &L, &err); break;
+    case 2: ok = amoeba::merge_launch_geometry(plan, align_bytes, &L, &err); break;
+    default: err = "kernel must be 0 (weights), 1 (KV regroup) or 2 (merge copy)"; break;
+  }
+  if (!ok) {
+    set_error("amoeba_plan_launch_shape: " + err);
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  out[0] = L.grid_x; out[1] = L.grid_y; out[2] = L.threads; out[3] = int64_t(L.items);
+  return AMOEBA_OK;
+}
+
 int amoeba_plan_tune(amoeba_plan_t* plan, int knob, int value) {
   if (!plan || value < 0) { set_error("amoeba_plan_tune: bad plan or value"); return AMOEBA_ERR_INVALID_ARG; }
   switch (knob) {
@@ -322,9 +367,9 @@ int amoeba_plan_tune(amoeba_plan_t* plan, int knob, int value) {
     case AMOEBA_TUNE_NONTEMPORAL: plan->tune.nontemporal = value; break;
     case AMOEBA_TUNE_KV_STAGED: plan->tune.kv_staged = value; break;
     case AMOEBA_TUNE_KV_BLOCKS_HINT: plan->tune.kv_blocks_hint = value; break;
-    case AMOEBA_TUNE_W_PART:
-      if (value > 2) { set_error("amoeba_plan_tune: AMOEBA_TUNE_W_PART takes 0, 1 or 2"); return AMOEBA_ERR_INVALID_ARG; }
-      plan->tune.w_part = value;
+    case AMOEBA_TUNE_KV_SMALL_TABLE:
+      if (value > 1) { set_error("amoeba_plan_tune: AMOEBA_TUNE_KV_SMALL_TABLE takes 0 or 1"); return AMOEBA_ERR_INVALID_ARG; }
+      plan->tune.kv_small = value;
       break;
     default: set_error("amoeba_plan_tune: unknown knob"); return AMOEBA_ERR_INVALID_ARG;
   }

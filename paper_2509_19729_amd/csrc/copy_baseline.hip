@@ -64,8 +64,9 @@ int launch_copy_baseline(void* dst, const void* src, size_t bytes, int threads, 
   if (threads != 64) threads = 256;
   const uint64_t n_vecs = bytes / 16, tile = uint64_t(threads) * unroll;
   const uint64_t n_tiles = (n_vecs + tile - 1) / tile;
-  uint64_t g = std::min<uint64_t>(n_tiles, (uint64_t(1) << 31) - 1);
+  uint64_t g = n_tiles;
   if (grid > 0) g = std::min<uint64_t>(g, uint64_t(grid));
+  g = clamp_grid_x(g, uint32_t(threads));
   char* d = static_cast<char*>(dst);
   const char* s = static_cast<const char*>(src);
   if (threads == 64) launch_unroll<64>(unroll, nt, uint32_t(g), stream, d, s, n_vecs, n_tiles);

@@ -5,6 +5,7 @@
 #include <string>
 
 #include "../../include/amoeba.h"
+#include "grid.h"
 
 struct amoeba_plan_s;
 
@@ -14,12 +15,23 @@ namespace amoeba {
 enum { kWsTotal = 0, kWsError = 1, kWsHeader = 8 };
 enum { kErrNegativeLen = 1, kErrRowTooShort = 2, kErrPoolTooSmall = 4, kErrBlockId = 8 };
 
+// part: AMOEBA_PART_ALL, _ATTENTION or _FFN.
 int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards, void* dst,
-                           hipStream_t stream, std::string* err);
+                           int part, hipStream_t stream, std::string* err);
 
-int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
+// ws: the workspace the kernels use, 8 + num_seqs + dst_pool_blocks int32 words on the
+// current device (the plan's own, or the static one of the entry point that allocates nothing).
+int launch_reshard_kv(const amoeba_plan_s* p, int32_t* ws, const void* const* src_blocks,
                       const int32_t* src_block_tables, const int32_t* seq_lens, void* dst_blocks,
                       int32_t* dst_block_tables, hipStream_t stream, std::string* err);
+
+// Launch geometry of the three copy kernels for pointers aligned to align_bytes (host only).
+bool weights_launch_geometry(const amoeba_plan_s* p, int align_bytes, LaunchShape* out,
+                             std::string* err);
+bool kv_launch_geometry(const amoeba_plan_s* p, int align_bytes, LaunchShape* out,
+                        std::string* err);
+bool merge_launch_geometry(const amoeba_plan_s* p, int align_bytes, LaunchShape* out,
+                           std::string* err);
 
 // int32 words of the merge workspace: header, chunk counts, one flag and one work-list
 // entry per new block id of the pool.

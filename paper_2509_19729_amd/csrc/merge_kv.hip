@@ -31,6 +31,7 @@
 #include <string>
 
 #include "device_common.h"
+#include "grid.h"
 #include "launch.h"
 #include "plan.h"
 
@@ -248,6 +249,57 @@ void launch_copy(bool nt, int waves, dim3 grid, hipStream_t stream, const MergeC
 
 }  // namespace
 
+namespace {
+
+struct MergeLaunch {
+  uint64_t tiles;   // 1 KiB tiles of one new block
+  uint32_t grid_x;  // tiles the grid covers per layer (launch_copy packs `waves` per workgroup)
+  int waves;        // wavefronts per workgroup
+};
+
+// One wavefront per tile.  The number of remote blocks is only known on the device, so
+// the grid covers the pool's capacity unless the caller gave a bound on the blocks in use
+// (amoeba_model_shape.kv_blocks_bound); past the grid, workgroups stride.
+bool merge_launch_shape(const amoeba_plan_s* p, int vec, MergeLaunch* out, std::string* err) {
+  const amoeba_model_shape& s = p->shape;
+  const uint64_t m = uint64_t(p->merge_factor);
+  const uint64_t slots = uint64_t(s.src_pool_blocks) * m;
+  const uint64_t sub_vecs = uint64_t(p->block_bytes_dst) / uint64_t(vec);
+  const uint64_t tiles = (sub_vecs + 63) / 64;
+  const uint64_t max_items = slots * tiles;
+  // item ids are 32-bit and a striding workgroup adds the grid size (at most 2^27) to one
+  if (sub_vecs >= (uint64_t(1) << 32) - 64 || max_items >= (uint64_t(1) << 31) ||
+      s.kv_layers > 65535) {
+    *err = "KV pool too large for 32-bit work indexing";
+    return false;
+  }
+  const int64_t bound = p->tune.kv_blocks_hint > 0 ? p->tune.kv_blocks_hint : s.kv_blocks_bound;
+  uint64_t grid = std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 27) / uint64_t(s.kv_layers));
+  if (p->tune.kv_grid > 0) grid = uint64_t(p->tune.kv_grid);
+  if (bound > 0) grid = std::min<uint64_t>(grid, std::max<uint64_t>(1, uint64_t(bound) * tiles));
+  grid = std::min<uint64_t>(grid, max_items);
+  // one wavefront per workgroup when the grid is tight, four when it covers the capacity
+  out->waves = p->tune.kv_threads == 256 ? 4 : p->tune.kv_threads == 64 ? 1 : (bound > 0 ? 1 : 4);
+  out->tiles = tiles;
+  out->grid_x = clamp_grid_x(std::max<uint64_t>(grid, 1), 64u);  // in tiles; <= 2^26 workgroups
+  return true;
+}
+
+}  // namespace
+
+bool merge_launch_geometry(const amoeba_plan_s* p, int align_bytes, LaunchShape* out,
+                           std::string* err) {
+  if (p->merge_factor < 2) { *err = "the plan is not an in-place merge"; return false; }
+  MergeLaunch L;
+  const int vec = common_alignment(uint64_t(p->block_bytes_dst) | uint64_t(align_bytes));
+  if (!merge_launch_shape(p, vec, &L, err)) return false;
+  out->grid_x = L.waves == 4 ? (L.grid_x + 3) / 4 : L.grid_x;
+  out->grid_y = uint32_t(p->shape.kv_layers);
+  out->threads = uint32_t(64 * L.waves);
+  out->items = uint64_t(p->shape.src_pool_blocks) * uint64_t(p->merge_factor) * L.tiles;
+  return true;
+}
+
 size_t merge_workspace_ints(int64_t pool_blocks, int m) {
   const size_t slots = size_t(pool_blocks) * size_t(m);
   return size_t(kWsHeader) + (slots + kWide - 1) / kWide + 1 + 2 * slots;
@@ -343,27 +395,11 @@ int launch_merge_kv_inplace(const amoeba_plan_s* p, void* local_pool,
   a.sub_vecs = uint32_t(a.sub_bytes / uint64_t(vec));
   a.n_inst = make_fastdiv(m);
   a.local_inst = g;
-  const uint64_t tiles = (uint64_t(a.sub_vecs) + 63) / 64;
-  a.tiles_per_sub = make_fastdiv(uint32_t(tiles));
-  const uint64_t max_items = uint64_t(slots) * tiles;
-  if (a.sub_bytes / uint64_t(vec) >= (uint64_t(1) << 32) - 64 ||
-      max_items >= (uint64_t(1) << 32) - (1 << 24) || s.kv_layers > 65535) {
-    *err = "KV pool too large for 32-bit work indexing";
-    return AMOEBA_ERR_INVALID_ARG;
-  }
-  // One wavefront per tile.  The number of remote blocks is only known on the device, so
-  // the grid covers the pool's capacity unless the caller gave a bound (see
-  // AMOEBA_TUNE_KV_BLOCKS_HINT); past the grid, workgroups stride.
-  uint64_t grid = std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 27) / uint64_t(s.kv_layers));
-  if (p->tune.kv_grid > 0) grid = uint64_t(p->tune.kv_grid);
-  grid = std::min<uint64_t>(grid, max_items);
-  if (p->tune.kv_blocks_hint > 0)
-    grid = std::min<uint64_t>(grid, std::max<uint64_t>(1, uint64_t(p->tune.kv_blocks_hint) * tiles));
-  const dim3 gr(uint32_t(grid), uint32_t(s.kv_layers));
-  // one wavefront per workgroup when the grid is tight, four when it covers the capacity
-  const int waves = p->tune.kv_threads == 256 ? 4
-                    : p->tune.kv_threads == 64 ? 1
-                    : (p->tune.kv_blocks_hint > 0 ? 1 : 4);
+  MergeLaunch L;
+  if (!merge_launch_shape(p, vec, &L, err)) return AMOEBA_ERR_INVALID_ARG;
+  a.tiles_per_sub = make_fastdiv(uint32_t(L.tiles));
+  const dim3 gr(L.grid_x, uint32_t(s.kv_layers));
+  const int waves = L.waves;
   switch (vec) {
     case 16: launch_copy<16>(nt, waves, gr, stream, a, ws, worklist); break;
     case 8: launch_copy<8>(nt, waves, gr, stream, a, ws, worklist); break;

@@ -59,6 +59,7 @@ bool build_plan(amoeba_plan_s* p, const amoeba_model_shape* shape, int k, int kp
   if (s.num_seqs < 0 || s.max_blocks_per_seq < 0 || s.src_pool_blocks < 0 ||
       s.dst_pool_blocks < 0)
     return fail(err, "negative table or pool size");
+  if (s.kv_blocks_bound < 0) return fail(err, "kv_blocks_bound is negative");
   if (s.src_pool_blocks > INT32_MAX || s.dst_pool_blocks > INT32_MAX)
     return fail(err, "a pool has more than 2^31-1 blocks (block ids are int32)");
   for (int tp : {k, kp}) {

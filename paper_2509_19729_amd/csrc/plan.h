@@ -48,9 +48,10 @@ struct ExpertGeom {
   int64_t layer;
 };
 
+// Launch-shape overrides of the measurement interface (0 = the built-in choice).
 struct Tuning {
   int w_grid = 0, w_unroll = 0, w_threads = 0, kv_grid = 0, kv_unroll = 0, kv_threads = 0,
-      nontemporal = 0, kv_staged = 0, kv_blocks_hint = 0, w_part = 0;
+      nontemporal = 0, kv_staged = 0, kv_blocks_hint = 0, kv_small = 0;
 };
 
 }  // namespace amoeba
@@ -72,6 +73,7 @@ struct amoeba_plan_s {
   int device;           // device the workspace lives on, -1 if none
   int n_cu;             // compute units of that device
   int32_t* workspace;   // [8 header][num_seqs bases][dst_pool_blocks source ids]
+  mutable const int32_t* status_ws;  // workspace of the last KV reshard enqueued on this plan
   size_t workspace_bytes;
   // in-place instance merge: m = dst_tp / src_tp when the plan qualifies, else 0
   int merge_factor;

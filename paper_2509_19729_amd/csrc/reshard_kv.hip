@@ -9,7 +9,7 @@
 // header-centric one ([head][K/V][token][d]) whose head sub-ranges are contiguous,
 // and the token-first one ([K/V][token][head][d]).
 //
-// Three kernels, no host round trip:
+// Three kernels, no host round trip (one when the table is small, see kv_small_kernel):
 //   kv_scan_kernel   one workgroup; nb_i = ceil(len_i / B), wavefront-level
 //                    inclusive scans joined through LDS, carried across chunks of
 //                    1024 sequences; validates lengths / row width / pool size.
@@ -30,6 +30,7 @@
 #include <string>
 
 #include "device_common.h"
+#include "grid.h"
 #include "launch.h"
 #include "plan.h"
 
@@ -143,15 +144,74 @@ struct KVArgs {
   FastDiv dv;                // vectors of one head vector (d * elem_bytes / VEC)
 };
 
+// Moves one tile (THREADS * UNROLL vectors, contiguous in the destination block) of new
+// block b, whose source block id is sb (negative: the id was out of range, nothing moves).
+// A lane turns its vector index into (head, K/V * token, d-offset) for the destination
+// layout, maps the head to (source rank, local head) and rebuilds the index for the source
+// layout; all loads of the tile are issued before its stores.
+template <int SL, int DL, int VEC, int THREADS, int UNROLL, bool NT>
+__device__ __forceinline__ void regroup_tile(const KVArgs& a, uint32_t layer, uint32_t b,
+                                             uint32_t tile, int32_t sb, uint32_t tid) {
+  using V = typename VecOf<VEC>::type;
+  constexpr uint32_t kTileVecs = THREADS * UNROLL;
+  const char* sp[UNROLL];
+  uint32_t dvec[UNROLL];
+  bool live[UNROLL];
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    const uint32_t v = tile * kTileVecs + u * THREADS + tid;
+    live[u] = v < a.block_vecs;
+    dvec[u] = v;
+    uint32_t hp, within, ct = 0, x = 0;  // within: index inside one header-centric head
+    if (DL == AMOEBA_KV_HEAD_MAJOR) {
+      hp = fd_div(v, a.head_vecs);
+      within = v - hp * a.head_vecs.d;
+      if (SL != AMOEBA_KV_HEAD_MAJOR) {
+        ct = fd_div(within, a.dv);
+        x = within - ct * a.dv.d;
+      }
+    } else {
+      const uint32_t q = fd_div(v, a.dv);
+      x = v - q * a.dv.d;
+      ct = fd_div(q, a.heads_dst);
+      hp = q - ct * a.heads_dst.d;
+      within = ct * a.dv.d + x;
+    }
+    const uint32_t h = a.head0 + hp;
+    const uint32_t s = fd_div(h, a.heads_src);
+    const uint32_t hs = h - s * a.heads_src.d;
+    const uint32_t svec = (SL == AMOEBA_KV_HEAD_MAJOR)
+                              ? hs * a.head_vecs.d + within
+                              : (ct * a.heads_src.d + hs) * a.dv.d + x;
+    // Source pool of the owning rank.  Nearly always one or two ranks feed a target
+    // rank; then the choice is a select between two scalar-loaded pointers and
+    // costs no memory access.
+    const char* pool;
+    if (a.n_src <= 2)
+      pool = (s == a.rank_lo) ? a.src_lo : a.src_hi;
+    else
+      pool = a.src[live[u] ? s : a.rank_lo];  // s < src_tp on live lanes
+    sp[u] = pool + uint64_t(svec) * VEC;
+  }
+  const uint64_t soff = uint64_t(layer) * a.src_layer_stride + uint64_t(sb) * a.src_block_bytes;
+  char* dp = a.dst + uint64_t(layer) * a.dst_layer_stride + uint64_t(b) * a.dst_block_bytes;
+  V val[UNROLL];
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    live[u] = live[u] && sb >= 0;
+    if (live[u]) val[u] = ld<NT, V>(sp[u] + soff);
+  }
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u)
+    if (live[u]) st<NT, V>(dp + uint64_t(dvec[u]) * VEC, val[u]);
+}
+
 // blockIdx.y = layer; blockIdx.x strides over (new block, tile) of that layer.
 // `ws` is only read here (the scan and table kernels that fill it have finished),
 // which lets the uniform lookups go through scalar loads.
 template <int SL, int DL, int VEC, int THREADS, int UNROLL, bool NT>
 __global__ void __launch_bounds__(THREADS)
 kv_regroup_kernel(const KVArgs a, const int32_t* __restrict__ ws) {
-  using V = typename VecOf<VEC>::type;
-  constexpr uint32_t kTileVecs = THREADS * UNROLL;
-  const uint32_t tid = threadIdx.x;
   const uint32_t layer = blockIdx.y;
   const uint32_t total = (uint32_t)ws[kWsTotal];
   const int32_t* __restrict__ worklist = ws + kWsHeader + a.num_seqs;
@@ -167,57 +227,84 @@ kv_regroup_kernel(const KVArgs a, const int32_t* __restrict__ ws) {
     const uint32_t b = fd_div(w, a.tiles_per_block);
     const uint32_t tile = w - b * a.tiles_per_block.d;
     const int32_t sb = worklist[b];  // -1: the source id was out of range, block is skipped
+    regroup_tile<SL, DL, VEC, THREADS, UNROLL, NT>(a, layer, b, tile, sb, threadIdx.x);
+  }
+}
 
-    const char* sp[UNROLL];
-    uint32_t dvec[UNROLL];
-    bool live[UNROLL];
+// The whole KV path in one launch, for small tables (at most 64 sequences and kSmallCells
+// table cells): a configuration of a few short sequences is bound by launch latency, and
+// three dependent launches cost three times one.  Every workgroup is one wavefront and
+// redoes the scan itself: lane i takes sequence i, the inclusive scan is six __shfl_up
+// steps, the sequence that owns new block b is found with one ballot.  Workgroup (0, 0)
+// alone writes the new table, checks every source id and writes the status words, so no
+// word is written by two workgroups and nothing has to be cleared beforehand.
+constexpr uint32_t kSmallSeqs = 64;
+constexpr uint32_t kSmallCells = 4096;
+
+template <int SL, int DL>
+__global__ void __launch_bounds__(64)
+kv_small_kernel(const KVArgs a, const int32_t* __restrict__ seq_lens,
+                const int32_t* __restrict__ src_table, int32_t* __restrict__ dst_table,
+                uint32_t row_width, uint32_t block_tokens, int64_t src_pool_blocks,
+                int64_t dst_pool_blocks, int32_t* __restrict__ ws) {
+  __shared__ int32_t base_s[kSmallSeqs], nb_s[kSmallSeqs];
+  const uint32_t lane = threadIdx.x;
+  const bool has_seq = lane < a.num_seqs;
+  const long long len = has_seq ? seq_lens[lane] : 0;
+  const bool negative = len < 0;
+  long long nb = negative ? 0 : (len + block_tokens - 1) / block_tokens;
+  const bool too_long = nb > (long long)row_width;
+  long long incl = nb;
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-      const uint32_t v = tile * kTileVecs + u * THREADS + tid;
-      live[u] = v < a.block_vecs;
-      dvec[u] = v;
-      uint32_t hp, within, ct = 0, x = 0;  // within: index inside one header-centric head
-      if (DL == AMOEBA_KV_HEAD_MAJOR) {
-        hp = fd_div(v, a.head_vecs);
-        within = v - hp * a.head_vecs.d;
-        if (SL != AMOEBA_KV_HEAD_MAJOR) {
-          ct = fd_div(within, a.dv);
-          x = within - ct * a.dv.d;
-        }
-      } else {
-        const uint32_t q = fd_div(v, a.dv);
-        x = v - q * a.dv.d;
-        ct = fd_div(q, a.heads_dst);
-        hp = q - ct * a.heads_dst.d;
-        within = ct * a.dv.d + x;
+  for (int off = 1; off < 64; off <<= 1) {
+    const long long up = __shfl_up(incl, off, 64);
+    if (lane >= (uint32_t)off) incl += up;
+  }
+  const long long total = __shfl(incl, 63, 64);
+  unsigned int err = (__ballot(negative) ? kErrNegativeLen : 0u) |
+                     (__ballot(too_long) ? kErrRowTooShort : 0u) |
+                     (total > dst_pool_blocks ? kErrPoolTooSmall : 0u);
+  if (!err) {  // then nb <= row_width and every base is below dst_pool_blocks < 2^31
+    base_s[lane] = (int32_t)(incl - nb);
+    nb_s[lane] = (int32_t)nb;
+  }
+  __syncthreads();
+
+  if (blockIdx.x == 0 && blockIdx.y == 0) {
+    const uint32_t cells = a.num_seqs * row_width;
+    bool bad = false;
+    for (uint32_t cell = lane; cell < cells; cell += 64) {
+      const uint32_t i = cell / row_width, j = cell - i * row_width;
+      int32_t out = -1;
+      if (!err && (int32_t)j < nb_s[i]) {
+        out = base_s[i] + (int32_t)j;
+        const int32_t sb = src_table[cell];
+        if (sb < 0 || (int64_t)sb >= src_pool_blocks) bad = true;
       }
-      const uint32_t h = a.head0 + hp;
-      const uint32_t s = fd_div(h, a.heads_src);
-      const uint32_t hs = h - s * a.heads_src.d;
-      const uint32_t svec = (SL == AMOEBA_KV_HEAD_MAJOR)
-                                ? hs * a.head_vecs.d + within
-                                : (ct * a.heads_src.d + hs) * a.dv.d + x;
-      // Source pool of the owning rank.  Nearly always one or two ranks feed a target
-      // rank; then the choice is a select between two scalar-loaded pointers and
-      // costs no memory access.
-      const char* pool;
-      if (a.n_src <= 2)
-        pool = (s == a.rank_lo) ? a.src_lo : a.src_hi;
-      else
-        pool = a.src[live[u] ? s : a.rank_lo];  // s < src_tp on live lanes
-      sp[u] = pool + uint64_t(svec) * VEC;
+      dst_table[cell] = out;
     }
-    const uint64_t soff = uint64_t(layer) * a.src_layer_stride + uint64_t(sb) * a.src_block_bytes;
-    char* dp = a.dst + uint64_t(layer) * a.dst_layer_stride + uint64_t(b) * a.dst_block_bytes;
-    V val[UNROLL];
-#pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-      live[u] = live[u] && sb >= 0;
-      if (live[u]) val[u] = ld<NT, V>(sp[u] + soff);
+    const bool any_bad = __ballot(bad) != 0;
+    if (lane == 0) {
+      ws[kWsTotal] = err ? 0 : (int32_t)total;
+      ws[kWsError] = (int32_t)(err | (any_bad ? (unsigned int)kErrBlockId : 0u));
     }
-#pragma unroll
-    for (int u = 0; u < UNROLL; ++u)
-      if (live[u]) st<NT, V>(dp + uint64_t(dvec[u]) * VEC, val[u]);
+  }
+  if (err) return;
+
+  const uint32_t layer = blockIdx.y;
+  const uint32_t n_items = (uint32_t)total * a.tiles_per_block.d;
+  const uint32_t my_base = has_seq ? (uint32_t)(incl - nb) : 0u, my_nb = has_seq ? (uint32_t)nb : 0u;
+  for (uint32_t w = blockIdx.x; w < n_items; w += gridDim.x) {
+    const uint32_t b = fd_div(w, a.tiles_per_block);
+    const uint32_t tile = w - b * a.tiles_per_block.d;
+    // the one sequence whose id range [base, base + nb) holds b
+    const unsigned long long owner = __ballot(b >= my_base && b - my_base < my_nb);
+    if (!owner) continue;  // cannot happen for b < total; keeps the lookup below in bounds
+    const uint32_t i = (uint32_t)__ffsll((long long)owner) - 1u;
+    int32_t sb = src_table[i * row_width + (b - (uint32_t)base_s[i])];
+    if (sb < 0 || (int64_t)sb >= src_pool_blocks) sb = -1;
+    sb = __builtin_amdgcn_readfirstlane(sb);
+    regroup_tile<SL, DL, 16, 64, 1, true>(a, layer, b, tile, sb, lane);
   }
 }
 
@@ -378,52 +465,29 @@ bool hip_ok(const char* what, std::string* err) {
   return false;
 }
 
-}  // namespace
+// Everything the host decides about the regroup launch, from the plan and the common
+// alignment of the call's pointers.
+struct KVLaunch {
+  bool staged = false;   // layout conversion through LDS
+  bool small = false;    // scan, table and regroup in one launch (kv_small_kernel)
+  int vec = 16, threads = 64, unroll = 1;  // unroll: vectors per lane (staged: per side)
+  uint64_t tiles_per_block = 0;
+  dim3 grid;
+  KVStagedGeom g;
+  size_t lds = 0;
+};
 
-int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
-                      const int32_t* src_block_tables, const int32_t* seq_lens, void* dst_blocks,
-                      int32_t* dst_block_tables, hipStream_t stream, std::string* err) {
+bool kv_launch_shape(const amoeba_plan_s* p, int vec, KVLaunch* out, std::string* err) {
   const amoeba_model_shape& s = p->shape;
-  if (!p->workspace) {
-    *err = "the plan has no device workspace (it was created without a GPU)";
-    return AMOEBA_ERR_HIP;
-  }
-  int current_device = -1;
-  if (hipGetDevice(&current_device) != hipSuccess || current_device != p->device) {
-    *err = "the current device is not the one the plan's workspace was allocated on";
-    return AMOEBA_ERR_INVALID_ARG;
-  }
-  const uint64_t cells = uint64_t(s.num_seqs) * uint64_t(s.max_blocks_per_seq);
-  if (cells >= (uint64_t(1) << 32) - kThreads) {
-    *err = "block table has 2^32 cells or more";
-    return AMOEBA_ERR_INVALID_ARG;
-  }
-  if (cells && (!src_block_tables || !seq_lens || !dst_block_tables)) {
-    *err = "table or length pointer is NULL";
-    return AMOEBA_ERR_INVALID_ARG;
-  }
-  const uint64_t src_layer = uint64_t(s.src_pool_blocks) * p->block_bytes_src,
-                 dst_layer = uint64_t(s.dst_pool_blocks) * p->block_bytes_dst;
-  const uint64_t src_bytes = src_layer * s.kv_layers, dst_bytes = dst_layer * s.kv_layers;
-  const uint64_t d0 = reinterpret_cast<uint64_t>(dst_blocks);
-  if (!d0 && dst_bytes) { *err = "dst_blocks is NULL"; return AMOEBA_ERR_INVALID_ARG; }
-
   const uint64_t head_vec_bytes = uint64_t(s.head_dim) * s.elem_bytes;
-  uint64_t bits = head_vec_bytes | d0;
-  KVArgs a;
-  for (int r = 0; r < AMOEBA_MAX_TP; ++r) a.src[r] = nullptr;
-  for (int r = 0; r < p->k; ++r) {
-    if (!(p->kv_rank_mask >> r & 1)) continue;
-    const uint64_t s0 = reinterpret_cast<uint64_t>(src_blocks[r]);
-    if (!s0 && src_bytes) { *err = "a needed source pool pointer is NULL"; return AMOEBA_ERR_INVALID_ARG; }
-    if (s0 < d0 + dst_bytes && d0 < s0 + src_bytes) {
-      *err = "dst_blocks overlaps a source pool (the regroup is out of place)";
-      return AMOEBA_ERR_INVALID_ARG;
-    }
-    bits |= s0;
-    a.src[r] = static_cast<const char*>(src_blocks[r]);
-  }
-  const int vec = common_alignment(bits);
+  const uint32_t B = uint32_t(s.kv_block_tokens);
+  const uint32_t dv = uint32_t(head_vec_bytes / vec);  // vectors of one head vector
+  const uint64_t block_vecs = uint64_t(p->block_bytes_dst) / vec;
+  const uint64_t cells = uint64_t(s.num_seqs) * uint64_t(s.max_blocks_per_seq);
+  // the caller's bound on the blocks in use (the shape's, unless a sweep overrides it)
+  const int64_t bound = p->tune.kv_blocks_hint > 0 ? p->tune.kv_blocks_hint : s.kv_blocks_bound;
+  KVLaunch L;
+  L.vec = vec;
   int unroll = p->tune.kv_unroll, threads = p->tune.kv_threads;
   if (vec != 16 || (unroll != 2 && unroll != 4)) unroll = 1;
   if (vec != 16) threads = 256;
@@ -433,67 +497,28 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
     // sized by the pool's capacity every idle workgroup costs dispatch time; 4 KiB tiles cut
     // that cost by four.  So: small tiles when the caller bounded the blocks in use, large
     // ones otherwise.
-    threads = p->tune.kv_blocks_hint > 0 ? 64 : 256;
-  const bool nt = p->tune.nontemporal != 2;
-
-  // 1. scan
-  hipLaunchKernelGGL(kv_scan_kernel, dim3(1), dim3(kScanThreads), 0, stream, seq_lens,
-                     uint32_t(s.num_seqs), uint32_t(s.max_blocks_per_seq),
-                     uint32_t(s.kv_block_tokens), int64_t(s.dst_pool_blocks), p->workspace);
-  if (!hip_ok("kv scan kernel launch failed", err)) return AMOEBA_ERR_HIP;
-  // 2. tables
-  if (cells) {
-    const uint32_t grid = uint32_t((cells + kThreads - 1) / kThreads);
-    hipLaunchKernelGGL(kv_table_kernel, dim3(grid), dim3(kThreads), 0, stream, seq_lens,
-                       src_block_tables, dst_block_tables, uint32_t(s.num_seqs),
-                       make_fastdiv(uint32_t(s.max_blocks_per_seq)), uint32_t(s.kv_block_tokens),
-                       int64_t(s.src_pool_blocks), p->workspace);
-    if (!hip_ok("kv table kernel launch failed", err)) return AMOEBA_ERR_HIP;
-  }
-  // 3. regroup
-  if (cells == 0 || s.dst_pool_blocks == 0) return AMOEBA_OK;
-  const uint32_t B = uint32_t(s.kv_block_tokens);
-  const uint32_t dv = uint32_t(head_vec_bytes / vec);  // vectors of one head vector
-  a.dst = static_cast<char*>(dst_blocks);
-  a.ws = p->workspace;
-  a.src_layer_stride = src_layer;
-  a.dst_layer_stride = dst_layer;
-  a.src_block_bytes = uint64_t(p->block_bytes_src);
-  a.dst_block_bytes = uint64_t(p->block_bytes_dst);
-  a.num_seqs = uint32_t(s.num_seqs);
-  a.head0 = uint32_t(p->rp * p->heads_dst);
-  a.rank_lo = a.head0 / uint32_t(p->heads_src);
-  a.rank_hi = (a.head0 + uint32_t(p->heads_dst) - 1) / uint32_t(p->heads_src);
-  a.n_src = a.rank_hi - a.rank_lo + 1;
-  a.src_lo = a.src[a.rank_lo];
-  a.src_hi = a.src[a.rank_hi];
-  a.heads_src = make_fastdiv(uint32_t(p->heads_src));
-  a.heads_dst = make_fastdiv(uint32_t(p->heads_dst));
-  a.dv = make_fastdiv(dv);
-  a.head_vecs = make_fastdiv(2u * B * dv);
-  const uint64_t block_vecs = uint64_t(p->block_bytes_dst) / vec;
-  a.block_vecs = uint32_t(block_vecs);
+    threads = bound > 0 ? 64 : 256;
 
   // Grid: one workgroup per tile of the pool's capacity (workgroups that stride over several
   // tiles measured 8 % slower), or of the caller's bound on the blocks in use; capped at 2^27
   // workgroups over all layers so that a huge, mostly empty pool does not pay for idle
-  // workgroups without limit.  Past the grid, workgroups stride.
-  auto grid_for = [&](uint64_t tiles_per_block, dim3* out) {
+  // workgroups without limit, and at the work-items one grid dimension can hold.  Past the
+  // grid, workgroups stride.
+  auto grid_for = [&](uint64_t tiles_per_block, uint32_t lanes, dim3* g) {
     const uint64_t max_items = uint64_t(s.dst_pool_blocks) * tiles_per_block;  // per layer
-    if (block_vecs >= (uint64_t(1) << 32) - 65536 ||
-        max_items >= (uint64_t(1) << 32) - (1 << 24) || s.kv_layers > 65535)
+    // item ids are 32-bit and a striding workgroup adds the grid size (at most 2^27) to one
+    if (block_vecs >= (uint64_t(1) << 32) - 65536 || max_items >= (uint64_t(1) << 31) ||
+        s.kv_layers > 65535)
       return false;
     uint64_t grid =
         std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 27) / uint64_t(s.kv_layers));
     if (p->tune.kv_grid > 0) grid = uint64_t(p->tune.kv_grid);
-    grid = std::min<uint64_t>(grid, max_items);
-    if (p->tune.kv_blocks_hint > 0)
-      grid = std::min<uint64_t>(
-          grid, std::max<uint64_t>(1, uint64_t(p->tune.kv_blocks_hint) * tiles_per_block));
-    *out = dim3(uint32_t(grid), uint32_t(s.kv_layers));
+    if (bound > 0)
+      grid = std::min<uint64_t>(grid, std::max<uint64_t>(1, uint64_t(bound) * tiles_per_block));
+    grid = grid_for_items(grid, max_items);
+    *g = dim3(clamp_grid_x(grid, lanes), uint32_t(s.kv_layers));
     return true;
   };
-  dim3 grid;
 
   // Converting between the layouts goes through LDS when one head vector is at most one
   // 128-byte cache line (see kv_regroup_staged_kernel): below a line the direct gather
@@ -526,23 +551,160 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
       tt = std::min<uint32_t>(std::max<uint32_t>(1, cap / (th * dv)), B);
       while (B % tt) --tt;
     }
-    KVStagedGeom g;
-    g.tile_tokens = tt;
-    g.tile_heads = th;
-    g.block_tokens = B;
-    g.tile_vecs = tt * th * dv;
-    g.token_groups = make_fastdiv(B / tt);
-    g.fd_tile_tokens = make_fastdiv(tt);
-    g.fd_tile_heads = make_fastdiv(th);
+    L.staged = true;
+    L.threads = st_threads;
+    L.unroll = st_iters;
+    L.g.tile_tokens = tt;
+    L.g.tile_heads = th;
+    L.g.block_tokens = B;
+    L.g.tile_vecs = tt * th * dv;
+    L.g.token_groups = make_fastdiv(B / tt);
+    L.g.fd_tile_tokens = make_fastdiv(tt);
+    L.g.fd_tile_heads = make_fastdiv(th);
     const uint64_t head_groups = (uint64_t(p->heads_dst) + th - 1) / th;
-    const uint64_t tiles_per_block = head_groups * 2 * (B / tt);
-    a.tiles_per_block = make_fastdiv(uint32_t(tiles_per_block));
-    if (!grid_for(tiles_per_block, &grid)) {
+    L.tiles_per_block = head_groups * 2 * (B / tt);
+    L.lds = size_t(L.g.tile_vecs) * 16;
+    if (!grid_for(L.tiles_per_block, uint32_t(st_threads), &L.grid)) {
       *err = "KV pool too large for 32-bit work indexing";
+      return false;
+    }
+    *out = L;
+    return true;
+  }
+
+  // A small table: scan, table and regroup in one launch of single-wavefront workgroups.
+  if (vec == 16 && p->tune.kv_small != 1 && p->tune.kv_unroll == 0 && p->tune.kv_threads == 0 &&
+      p->tune.nontemporal != 2 && cells > 0 && cells <= kSmallCells &&
+      uint32_t(s.num_seqs) <= kSmallSeqs && s.dst_pool_blocks > 0) {
+    L.small = true;
+    threads = 64;
+    unroll = 1;
+  }
+  L.threads = threads;
+  L.unroll = unroll;
+  const uint64_t tile_vecs = uint64_t(threads) * unroll;
+  L.tiles_per_block = (block_vecs + tile_vecs - 1) / tile_vecs;
+  if (!grid_for(L.tiles_per_block, uint32_t(threads), &L.grid)) {
+    *err = "KV pool too large for 32-bit work indexing";
+    return false;
+  }
+  *out = L;
+  return true;
+}
+
+}  // namespace
+
+bool kv_launch_geometry(const amoeba_plan_s* p, int align_bytes, LaunchShape* out,
+                        std::string* err) {
+  const uint64_t head_vec_bytes = uint64_t(p->shape.head_dim) * p->shape.elem_bytes;
+  const int vec = common_alignment(head_vec_bytes | uint64_t(align_bytes));
+  KVLaunch L;
+  if (!kv_launch_shape(p, vec, &L, err)) return false;
+  out->grid_x = L.grid.x;
+  out->grid_y = L.grid.y;
+  out->threads = uint32_t(L.threads);
+  out->items = uint64_t(p->shape.dst_pool_blocks) * L.tiles_per_block;
+  return true;
+}
+
+int launch_reshard_kv(const amoeba_plan_s* p, int32_t* ws, const void* const* src_blocks,
+                      const int32_t* src_block_tables, const int32_t* seq_lens, void* dst_blocks,
+                      int32_t* dst_block_tables, hipStream_t stream, std::string* err) {
+  const amoeba_model_shape& s = p->shape;
+  const uint64_t cells = uint64_t(s.num_seqs) * uint64_t(s.max_blocks_per_seq);
+  if (cells >= (uint64_t(1) << 32) - kThreads) {
+    *err = "block table has 2^32 cells or more";
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  if (cells && (!src_block_tables || !seq_lens || !dst_block_tables)) {
+    *err = "table or length pointer is NULL";
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  const uint64_t src_layer = uint64_t(s.src_pool_blocks) * p->block_bytes_src,
+                 dst_layer = uint64_t(s.dst_pool_blocks) * p->block_bytes_dst;
+  const uint64_t src_bytes = src_layer * s.kv_layers, dst_bytes = dst_layer * s.kv_layers;
+  const uint64_t d0 = reinterpret_cast<uint64_t>(dst_blocks);
+  if (!d0 && dst_bytes) { *err = "dst_blocks is NULL"; return AMOEBA_ERR_INVALID_ARG; }
+
+  const uint64_t head_vec_bytes = uint64_t(s.head_dim) * s.elem_bytes;
+  uint64_t bits = head_vec_bytes | d0;
+  KVArgs a;
+  for (int r = 0; r < AMOEBA_MAX_TP; ++r) a.src[r] = nullptr;
+  for (int r = 0; r < p->k; ++r) {
+    if (!(p->kv_rank_mask >> r & 1)) continue;
+    const uint64_t s0 = reinterpret_cast<uint64_t>(src_blocks[r]);
+    if (!s0 && src_bytes) { *err = "a needed source pool pointer is NULL"; return AMOEBA_ERR_INVALID_ARG; }
+    if (s0 < d0 + dst_bytes && d0 < s0 + src_bytes) {
+      *err = "dst_blocks overlaps a source pool (the regroup is out of place)";
       return AMOEBA_ERR_INVALID_ARG;
     }
-    const size_t lds = size_t(g.tile_vecs) * 16;
-    const bool src_hm = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR;
+    bits |= s0;
+    a.src[r] = static_cast<const char*>(src_blocks[r]);
+  }
+  const int vec = common_alignment(bits);
+  KVLaunch L;
+  if (!kv_launch_shape(p, vec, &L, err)) return AMOEBA_ERR_INVALID_ARG;
+  const bool nt = p->tune.nontemporal != 2;
+
+  const uint32_t B = uint32_t(s.kv_block_tokens);
+  const uint32_t dv = uint32_t(head_vec_bytes / vec);  // vectors of one head vector
+  a.dst = static_cast<char*>(dst_blocks);
+  a.ws = ws;
+  a.src_layer_stride = src_layer;
+  a.dst_layer_stride = dst_layer;
+  a.src_block_bytes = uint64_t(p->block_bytes_src);
+  a.dst_block_bytes = uint64_t(p->block_bytes_dst);
+  a.num_seqs = uint32_t(s.num_seqs);
+  a.head0 = uint32_t(p->rp * p->heads_dst);
+  a.rank_lo = a.head0 / uint32_t(p->heads_src);
+  a.rank_hi = (a.head0 + uint32_t(p->heads_dst) - 1) / uint32_t(p->heads_src);
+  a.n_src = a.rank_hi - a.rank_lo + 1;
+  a.src_lo = a.src[a.rank_lo];
+  a.src_hi = a.src[a.rank_hi];
+  a.heads_src = make_fastdiv(uint32_t(p->heads_src));
+  a.heads_dst = make_fastdiv(uint32_t(p->heads_dst));
+  a.dv = make_fastdiv(dv);
+  a.head_vecs = make_fastdiv(2u * B * dv);
+  a.block_vecs = uint32_t(uint64_t(p->block_bytes_dst) / vec);
+  a.tiles_per_block = make_fastdiv(uint32_t(L.tiles_per_block));
+  const bool sh = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR, dh = s.kv_layout_dst == AMOEBA_KV_HEAD_MAJOR;
+
+  if (L.small) {
+#define AMOEBA_SMALL(SLAY, DLAY)                                                                  \
+  hipLaunchKernelGGL((kv_small_kernel<SLAY, DLAY>), L.grid, dim3(64), 0, stream, a, seq_lens,     \
+                     src_block_tables, dst_block_tables, uint32_t(s.max_blocks_per_seq), B,       \
+                     int64_t(s.src_pool_blocks), int64_t(s.dst_pool_blocks), ws)
+    if (sh && dh) AMOEBA_SMALL(AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_HEAD_MAJOR);
+    else if (sh) AMOEBA_SMALL(AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR);
+    else if (dh) AMOEBA_SMALL(AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR);
+    else AMOEBA_SMALL(AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_TOKEN_MAJOR);
+#undef AMOEBA_SMALL
+    if (!hip_ok("kv small-table kernel launch failed", err)) return AMOEBA_ERR_HIP;
+    return AMOEBA_OK;
+  }
+
+  // 1. scan
+  hipLaunchKernelGGL(kv_scan_kernel, dim3(1), dim3(kScanThreads), 0, stream, seq_lens,
+                     uint32_t(s.num_seqs), uint32_t(s.max_blocks_per_seq),
+                     uint32_t(s.kv_block_tokens), int64_t(s.dst_pool_blocks), ws);
+  if (!hip_ok("kv scan kernel launch failed", err)) return AMOEBA_ERR_HIP;
+  // 2. tables
+  if (cells) {
+    const uint32_t grid = uint32_t((cells + kThreads - 1) / kThreads);
+    hipLaunchKernelGGL(kv_table_kernel, dim3(grid), dim3(kThreads), 0, stream, seq_lens,
+                       src_block_tables, dst_block_tables, uint32_t(s.num_seqs),
+                       make_fastdiv(uint32_t(s.max_blocks_per_seq)), uint32_t(s.kv_block_tokens),
+                       int64_t(s.src_pool_blocks), ws);
+    if (!hip_ok("kv table kernel launch failed", err)) return AMOEBA_ERR_HIP;
+  }
+  // 3. regroup
+  if (cells == 0 || s.dst_pool_blocks == 0) return AMOEBA_OK;
+
+  if (L.staged) {
+    const KVStagedGeom& g = L.g;
+    const dim3 grid = L.grid;
+    const size_t lds = L.lds;
+    const bool src_hm = sh;
 #define AMOEBA_STAGED(T, I)                                                                       \
   do {                                                                                            \
     if (src_hm && nt)                                                                             \
@@ -562,14 +724,14 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
                                                    false, T, I>),                                 \
                          grid, dim3(T), lds, stream, a, g, a.ws);                                 \
   } while (0)
-    if (st_threads == 64) {
-      switch (st_iters) {
+    if (L.threads == 64) {
+      switch (L.unroll) {
         case 1: AMOEBA_STAGED(64, 1); break;
         case 2: AMOEBA_STAGED(64, 2); break;
         default: AMOEBA_STAGED(64, 4); break;
       }
     } else {
-      switch (st_iters) {
+      switch (L.unroll) {
         case 1: AMOEBA_STAGED(256, 1); break;
         case 2: AMOEBA_STAGED(256, 2); break;
         default: AMOEBA_STAGED(256, 4); break;
@@ -580,22 +742,14 @@ int launch_reshard_kv(const amoeba_plan_s* p, const void* const* src_blocks,
     return AMOEBA_OK;
   }
 
-  const uint64_t tile_vecs = uint64_t(threads) * unroll;
-  const uint64_t tiles_per_block = (block_vecs + tile_vecs - 1) / tile_vecs;
-  a.tiles_per_block = make_fastdiv(uint32_t(tiles_per_block));
-  if (!grid_for(tiles_per_block, &grid)) {
-    *err = "KV pool too large for 32-bit work indexing";
-    return AMOEBA_ERR_INVALID_ARG;
-  }
-  const bool sh = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR, dh = s.kv_layout_dst == AMOEBA_KV_HEAD_MAJOR;
   if (sh && dh)
-    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, threads, unroll, nt, grid, stream, a);
+    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, L.threads, L.unroll, nt, L.grid, stream, a);
   else if (sh && !dh)
-    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, threads, unroll, nt, grid, stream, a);
+    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, L.threads, L.unroll, nt, L.grid, stream, a);
   else if (!sh && dh)
-    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, threads, unroll, nt, grid, stream, a);
+    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, L.threads, L.unroll, nt, L.grid, stream, a);
   else
-    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, threads, unroll, nt, grid, stream, a);
+    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, L.threads, L.unroll, nt, L.grid, stream, a);
   if (!hip_ok("kv regroup kernel launch failed", err)) return AMOEBA_ERR_HIP;
   return AMOEBA_OK;
 }

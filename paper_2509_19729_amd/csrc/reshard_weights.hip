@@ -25,6 +25,7 @@
 #include <vector>
 
 #include "device_common.h"
+#include "grid.h"
 #include "launch.h"
 #include "plan.h"
 
@@ -136,19 +137,120 @@ void dispatch(int vec, int threads, int unroll, bool nt, dim3 grid, hipStream_t 
 
 }  // namespace
 
-int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards, void* dst,
-                           hipStream_t stream, std::string* err) {
-  const int64_t src_layer = p->src_layer_bytes, dst_layer = p->dst_layer_bytes;
-  const uint64_t src_bytes = uint64_t(src_layer) * p->shape.n_layers,
-                 dst_bytes = uint64_t(dst_layer) * p->shape.n_layers;
+// Tile geometry of one launch over `chosen` segments: fills the kernel's segment table
+// (sources left null when src_shards is null) and returns the tiles per layer, or -1.
+namespace {
 
-  // widest access every address of this call is aligned to
-  uint64_t bits = uint64_t(src_layer) | uint64_t(dst_layer) | reinterpret_cast<uint64_t>(dst);
+struct WShape {
+  int vec, threads, unroll;
+  bool nt;
+};
+
+WShape weights_shape(const amoeba_plan_s* p, int vec) {
+  WShape w;
+  w.vec = vec;
+  w.unroll = p->tune.w_unroll;
+  w.threads = p->tune.w_threads;
+  if (vec != 16 || (w.unroll != 2 && w.unroll != 4 && w.unroll != 8)) w.unroll = 1;
+  if (vec != 16) w.threads = 256;
+  else if (w.threads != 128 && w.threads != 256) w.threads = 64;  // one wavefront per 1 KiB tile
+  w.nt = p->tune.nontemporal != 2;
+  return w;
+}
+
+// Alignment every offset, run and pitch of the plan's segments allows (with the layer strides).
+uint64_t plan_alignment_bits(const amoeba_plan_s* p) {
+  uint64_t bits = uint64_t(p->src_layer_bytes) | uint64_t(p->dst_layer_bytes);
   for (const Segment& g : p->segments) {
     bits |= uint64_t(g.dst_off) | uint64_t(g.run);
     if (g.src_rank >= 0) bits |= uint64_t(g.src_off);
     if (g.rows > 1) bits |= uint64_t(g.src_pitch) | uint64_t(g.dst_pitch);
   }
+  return bits;
+}
+
+std::vector<Segment> chosen_segments(const amoeba_plan_s* p, int part) {
+  std::vector<Segment> chosen;
+  for (const Segment& g : p->segments)
+    if (part == AMOEBA_PART_ALL || part == g.part + 1) chosen.push_back(g);
+  return chosen;
+}
+
+// Fills the tile table of segments [first, first + n_seg) and returns the tiles of one layer;
+// false if a segment does not fit 32-bit tile indexing.
+bool tile_table(const std::vector<Segment>& chosen, size_t first, uint32_t n_seg, const WShape& w,
+                const void* const* src_shards, WArgs* a, uint64_t* tiles_out, std::string* err) {
+  const uint64_t tile_vecs = uint64_t(w.threads) * w.unroll;
+  uint64_t tiles = 0;
+  for (uint32_t i = 0; i < n_seg; ++i) {
+    const Segment& g = chosen[first + i];
+    const uint64_t row_vecs = uint64_t(g.run) / w.vec, total = row_vecs * uint64_t(g.rows);
+    const bool strided = g.rows > 1;
+    if (total >= (uint64_t(1) << 32) - 65536 ||
+        (strided && (uint64_t(g.src_pitch) >= (uint64_t(1) << 32) ||
+                     uint64_t(g.dst_pitch) >= (uint64_t(1) << 32)))) {
+      *err = "a weight segment is too large for 32-bit tile indexing";
+      return false;
+    }
+    WSeg& s = a->seg[i];
+    s.src = (g.src_rank < 0 || !src_shards)
+                ? nullptr  // a gap of a padded target: zeros
+                : static_cast<const char*>(src_shards[g.src_rank]) + g.src_off;
+    s.dst_off = g.dst_off;
+    s.src_pitch = strided ? uint32_t(g.src_pitch) : 0;  // a single row never uses its pitch
+    s.dst_pitch = strided ? uint32_t(g.dst_pitch) : 0;
+    s.total_vecs = uint32_t(total);
+    s.row_vecs = make_fastdiv(uint32_t(row_vecs));
+    a->tile_begin[i] = uint32_t(tiles);
+    tiles += (total + tile_vecs - 1) / tile_vecs;
+  }
+  *tiles_out = tiles;
+  return true;
+}
+
+// One workgroup per tile, up to what one grid dimension holds; past it the workgroups stride.
+bool weights_grid(const amoeba_plan_s* p, uint64_t tiles_per_layer, const WShape& w,
+                  uint64_t* total_tiles, uint32_t* grid, std::string* err) {
+  *total_tiles = tiles_per_layer * uint64_t(p->shape.n_layers);
+  // Tile ids are 32-bit and a striding workgroup adds the grid size to one: both stay below
+  // 2^32 with at most 2^31 tiles (2 TiB of 1 KiB tiles) and a grid of at most 2^26.
+  if (*total_tiles >= (uint64_t(1) << 31)) {
+    *err = "too many tiles for one launch";
+    return false;
+  }
+  uint64_t want = *total_tiles;
+  if (p->tune.w_grid > 0) want = std::min<uint64_t>(want, uint64_t(p->tune.w_grid));
+  *grid = clamp_grid_x(want, uint32_t(w.threads));  // (a sweep's grid is taken as given)
+  return true;
+}
+
+}  // namespace
+
+bool weights_launch_geometry(const amoeba_plan_s* p, int align_bytes, LaunchShape* out,
+                             std::string* err) {
+  const WShape w = weights_shape(p, common_alignment(plan_alignment_bits(p) | uint64_t(align_bytes)));
+  const std::vector<Segment> chosen = chosen_segments(p, AMOEBA_PART_ALL);
+  WArgs a;
+  uint64_t tiles = 0, total = 0;
+  uint32_t grid = 0;
+  const uint32_t n_seg = uint32_t(std::min<size_t>(kMaxSegs, chosen.size()));
+  if (!tile_table(chosen, 0, n_seg, w, nullptr, &a, &tiles, err)) return false;
+  if (!weights_grid(p, tiles, w, &total, &grid, err)) return false;
+  out->grid_x = total ? grid : 0;
+  out->grid_y = 1;
+  out->threads = uint32_t(w.threads);
+  out->items = total;
+  return true;
+}
+
+int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards, void* dst,
+                           int part, hipStream_t stream, std::string* err) {
+  const int64_t src_layer = p->src_layer_bytes, dst_layer = p->dst_layer_bytes;
+  const uint64_t src_bytes = uint64_t(src_layer) * p->shape.n_layers,
+                 dst_bytes = uint64_t(dst_layer) * p->shape.n_layers;
+
+  // widest access every address of this call is aligned to
+  uint64_t bits = plan_alignment_bits(p) | reinterpret_cast<uint64_t>(dst);
   const uint64_t d0 = reinterpret_cast<uint64_t>(dst);
   for (int r = 0; r < p->k; ++r) {
     if (!(p->weight_rank_mask >> r & 1)) continue;
@@ -160,18 +262,9 @@ int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards
     }
     bits |= s0;
   }
-  const int vec = common_alignment(bits);
-  int unroll = p->tune.w_unroll, threads = p->tune.w_threads;
-  if (vec != 16 || (unroll != 2 && unroll != 4 && unroll != 8)) unroll = 1;
-  if (vec != 16) threads = 256;
-  else if (threads != 128 && threads != 256) threads = 64;  // one wavefront per 1 KiB tile
-  const bool nt = p->tune.nontemporal != 2;
-  const uint64_t tile_vecs = uint64_t(threads) * unroll;
+  const WShape w = weights_shape(p, common_alignment(bits));
 
-  // AMOEBA_TUNE_W_PART: move only the attention tensors (1) or only the FFN tensors (2)
-  std::vector<Segment> chosen;
-  for (const Segment& g : p->segments)
-    if (p->tune.w_part == 0 || p->tune.w_part == g.part + 1) chosen.push_back(g);
+  const std::vector<Segment> chosen = chosen_segments(p, part);
   const size_t n = chosen.size();
   for (size_t first = 0; first < n; first += kMaxSegs) {
     WArgs a;
@@ -179,39 +272,14 @@ int launch_reshard_weights(const amoeba_plan_s* p, const void* const* src_shards
     a.src_layer_stride = src_layer;
     a.dst_layer_stride = dst_layer;
     a.n_seg = uint32_t(std::min<size_t>(kMaxSegs, n - first));
-    uint64_t tiles = 0;
-    for (uint32_t i = 0; i < a.n_seg; ++i) {
-      const Segment& g = chosen[first + i];
-      const uint64_t row_vecs = uint64_t(g.run) / vec, total = row_vecs * uint64_t(g.rows);
-      const bool strided = g.rows > 1;
-      if (total >= (uint64_t(1) << 32) - 65536 ||
-          (strided && (uint64_t(g.src_pitch) >= (uint64_t(1) << 32) ||
-                       uint64_t(g.dst_pitch) >= (uint64_t(1) << 32)))) {
-        *err = "a weight segment is too large for 32-bit tile indexing";
-        return AMOEBA_ERR_INVALID_ARG;
-      }
-      WSeg& s = a.seg[i];
-      s.src = g.src_rank < 0 ? nullptr  // a gap of a padded target: zeros
-                             : static_cast<const char*>(src_shards[g.src_rank]) + g.src_off;
-      s.dst_off = g.dst_off;
-      s.src_pitch = strided ? uint32_t(g.src_pitch) : 0;  // a single row never uses its pitch
-      s.dst_pitch = strided ? uint32_t(g.dst_pitch) : 0;
-      s.total_vecs = uint32_t(total);
-      s.row_vecs = make_fastdiv(uint32_t(row_vecs));
-      a.tile_begin[i] = uint32_t(tiles);
-      tiles += (total + tile_vecs - 1) / tile_vecs;
-    }
-    const uint64_t total_tiles = tiles * uint64_t(p->shape.n_layers);
-    if (total_tiles >= (uint64_t(1) << 31)) {
-      *err = "too many tiles for one launch";
-      return AMOEBA_ERR_INVALID_ARG;
-    }
+    uint64_t tiles = 0, total_tiles = 0;
+    uint32_t grid = 0;
+    if (!tile_table(chosen, first, a.n_seg, w, src_shards, &a, &tiles, err)) return AMOEBA_ERR_INVALID_ARG;
+    if (!weights_grid(p, tiles, w, &total_tiles, &grid, err)) return AMOEBA_ERR_INVALID_ARG;
     if (total_tiles == 0) continue;
     a.total_tiles = uint32_t(total_tiles);
     a.tiles_per_layer = make_fastdiv(uint32_t(tiles));
-    uint64_t grid = total_tiles;
-    if (p->tune.w_grid > 0) grid = std::min<uint64_t>(grid, uint64_t(p->tune.w_grid));
-    dispatch(vec, threads, unroll, nt, dim3(uint32_t(grid)), stream, a);
+    dispatch(w.vec, w.threads, w.unroll, w.nt, dim3(grid), stream, a);
     const hipError_t rc = hipGetLastError();
     if (rc != hipSuccess) {
       *err = std::string("weight kernel launch failed: ") + hipGetErrorString(rc);

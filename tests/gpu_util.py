@@ -65,11 +65,14 @@ def gpu_reshard_weights(m: oracle.Model, k, kp, rp, src_np, tune=None, sentinel=
 
 
 def gpu_reshard_kv(kv: oracle.KV, k, kp, rp, src_pools_np, table_np, lens_np, tune=None,
-                   sentinel=0xA7):
+                   sentinel=0xA7, bound=0):
     """Returns (status, dst_pool, dst_table, total, guards_intact); the destination pool
-    starts filled with `sentinel` bytes so untouched blocks can be compared too."""
+    starts filled with `sentinel` bytes so untouched blocks can be compared too.  `bound`
+    goes into the shape's kv_blocks_bound."""
     dt = oracle.elem_dtype(kv.elem_bytes)
-    plan = ab.amoeba_plan(shape_from(model_for_kv(kv), kv), k, kp, rp)
+    shape = shape_from(model_for_kv(kv), kv)
+    shape.kv_blocks_bound = bound
+    plan = ab.amoeba_plan(shape, k, kp, rp)
     for knob, val in (tune or {}).items():
         ab.amoeba_plan_tune(plan, knob, val)
     bb = ab.amoeba_plan_kv_block_bytes(plan, 1)

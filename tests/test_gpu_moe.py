@@ -117,17 +117,16 @@ def test_moe_real_expert_shape_with_2mib_pages():
 
 def test_moe_attention_half_only_for_a_scale_up():
     """A scale-up whose experts stay where they are (zero-copy view) moves only the attention
-    tensors: with AMOEBA_TUNE_W_PART = 1 the expert part of the target is not written."""
+    tensors: with AMOEBA_PART_ATTENTION the expert part of the target is not written."""
     m = oracle.Model(n_layers=2, hidden=64, n_q_heads=8, n_kv_heads=4, head_dim=8, ffn_dim=24)
     x = oracle.Moe(8, 256, True, True)
     src = sources(m, x, 1, seed=8)
     st, want = oracle.reshard_weights_moe(m, x, 1, 4, 3, src)
     plan = ab.amoeba_plan(shape(m, x), 1, 4, 3)
-    ab.amoeba_plan_tune(plan, ab.TUNE_W_PART, 1)
     n = ab.amoeba_plan_shard_bytes(plan, 1)
     own, first, tensor, slot = ab.amoeba_plan_expert_info(plan, 1)
     out = torch.full((n,), 0x5C, dtype=torch.uint8, device="cuda")
-    ab.amoeba_reshard_weights(plan, [to_dev(src[0])], out)
+    ab.amoeba_reshard_weights_part(plan, [to_dev(src[0])], out, ab.PART_ATTENTION)
     torch.cuda.synchronize()
     got = out.cpu().numpy().reshape(m.n_layers, -1)
     w = want.view(np.uint8).reshape(m.n_layers, -1)

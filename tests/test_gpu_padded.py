@@ -105,7 +105,7 @@ def test_padded_unaligned_partitions_with_2mib_pages():
 
 
 def test_moving_only_the_attention_part_or_only_the_ffn_part():
-    """AMOEBA_TUNE_W_PART splits one reshard in two disjoint halves: the attention tensors and
+    """amoeba_reshard_weights_part splits one reshard in two disjoint halves: the attention tensors and
     the FFN tensors.  Each half leaves the other half's bytes alone; together they give the
     oracle's shard.  (A padded scale-up uses the attention half only: its FFN is a view.)"""
     m = oracle.Model(n_layers=2, hidden=64, n_q_heads=8, n_kv_heads=4, head_dim=8, ffn_dim=96)
@@ -121,10 +121,9 @@ def test_moving_only_the_attention_part_or_only_the_ffn_part():
         n = ab.amoeba_plan_shard_bytes(plan, 1)
         dev = [to_dev(a) for a in src]
         halves = []
-        for part in (1, 2):
-            ab.amoeba_plan_tune(plan, ab.TUNE_W_PART, part)
+        for part in (ab.PART_ATTENTION, ab.PART_FFN):
             out = torch.full((n,), 0x5C, dtype=torch.uint8, device="cuda")
-            ab.amoeba_reshard_weights(plan, dev, out)
+            ab.amoeba_reshard_weights_part(plan, dev, out, part)
             torch.cuda.synchronize()
             halves.append(out.cpu().numpy())
         a, f = halves

@@ -164,10 +164,11 @@ def kv_case(k, lens, lay_s, lay_d, n_heads=8, d=8, B=4, layers=2, seed=0, slack=
     return cfg, pools, table, lens
 
 
-def check_kv(cfg, k, kp, rp, pools, table, lens, tune=None, expect=oracle.OK):
+def check_kv(cfg, k, kp, rp, pools, table, lens, tune=None, expect=oracle.OK, bound=0):
+    """The library against the oracle, twice: with the launch path the library picks (small
+    tables take one fused launch) and with the three-kernel scan / table / regroup path
+    forced, so that both are compared on every case."""
     sent = 0xA7
-    st, got_pool, got_table, total, intact = gpu_reshard_kv(cfg, k, kp, rp, pools, table, lens,
-                                                            tune=tune, sentinel=sent)
     be = oracle.kv_block_elems(cfg, kp)
     want_pool = np.full((cfg.kv_layers, cfg.dst_pool_blocks, be),
                         sentinel_elem(cfg.elem_bytes, sent), dtype=oracle.elem_dtype(cfg.elem_bytes))
@@ -175,11 +176,15 @@ def check_kv(cfg, k, kp, rp, pools, table, lens, tune=None, expect=oracle.OK):
     assert ost == expect
     code = {oracle.OK: ab.OK, oracle.ERR_OVERFLOW: ab.ERR_OVERFLOW,
             oracle.ERR_BLOCK_ID: ab.ERR_BLOCK_ID}[ost]
-    assert st == code
-    assert intact, "bytes outside the destination pool were written"
-    np.testing.assert_array_equal(got_table, want_table)
-    assert total == want_total
-    np.testing.assert_array_equal(got_pool, want_pool)
+    for path in ({}, {ab.TUNE_KV_SMALL_TABLE: 1}):
+        st, got_pool, got_table, total, intact = gpu_reshard_kv(
+            cfg, k, kp, rp, pools, table, lens, tune={**(tune or {}), **path}, sentinel=sent,
+            bound=bound)
+        assert st == code, path
+        assert intact, "bytes outside the destination pool were written"
+        np.testing.assert_array_equal(got_table, want_table)
+        assert total == want_total
+        np.testing.assert_array_equal(got_pool, want_pool)
 
 
 LENS = [13, 1, 8, 0, 22, 5, 16]
@@ -261,14 +266,15 @@ def test_kv_staged_kernel_launch_shapes(threads, unroll):
 
 @pytest.mark.parametrize("hint", [1, 37, 10_000])
 def test_kv_blocks_in_use_hint_only_changes_the_launch_shape(hint):
-    """The hint bounds the grid; too small a hint makes workgroups stride, too large leaves
-    some idle.  The result is the same either way."""
+    """amoeba_model_shape.kv_blocks_bound sizes the grid; a bound that is too small makes
+    workgroups stride, one that is too large leaves some idle.  The result is the same."""
     for lay_s, lay_d in [(HM, HM), (TM, HM)]:
         cfg, pools, table, lens = kv_case(2, [40, 100, 7, 33], lay_s, lay_d, n_heads=10, d=64,
                                           B=16, layers=3, seed=hint)
-        check_kv(cfg, 2, 1, 0, pools, table, lens, tune={ab.TUNE_KV_BLOCKS_HINT: hint})
-        check_kv(cfg, 2, 5, 2, pools, table, lens,
-                 tune={ab.TUNE_KV_BLOCKS_HINT: hint, ab.TUNE_KV_STAGED: 1})
+        check_kv(cfg, 2, 1, 0, pools, table, lens, bound=hint)
+        check_kv(cfg, 2, 5, 2, pools, table, lens, bound=hint, tune={ab.TUNE_KV_STAGED: 1})
+        # a sweep's override of the shape's bound
+        check_kv(cfg, 2, 1, 0, pools, table, lens, bound=3, tune={ab.TUNE_KV_BLOCKS_HINT: hint})
 
 
 def test_kv_more_than_one_scan_chunk():

@@ -9,27 +9,32 @@ import tempfile
 from paper_2509_19729_amd import binding as ab
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "amoeba.h")
+HEADERS = {"amoeba.h": ab.EXPORTS, "amoeba_measure.h": ab.MEASURE_EXPORTS}
 
 
-def declared_functions():
-    text = open(HEADER).read()
+def declared_functions(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(amoeba_[a-z_0-9]+)\s*\(", text)))
 
 
 def test_header_compiles_as_c99_and_links_against_the_library():
-    names = declared_functions()
-    assert set(names) == set(ab.EXPORTS)
+    names = []
+    for header, exports in HEADERS.items():
+        found = declared_functions(header)
+        assert set(found) == set(exports), header
+        names += found
     body = "\n".join(f"  sink((void*)&{n});" for n in names)
     src = f"""#include "amoeba.h"
+#include "amoeba_measure.h"
 static void sink(void* p) {{ (void)p; }}
 int main(void) {{
   amoeba_model_shape s = {{0}};
-  s.n_layers = 1; s.elem_bytes = 2; s.n_experts = 0; s.pad_page_bytes = 0;
+  s.n_layers = 1; s.elem_bytes = 2; s.n_experts = 0; s.pad_page_bytes = 0; s.kv_blocks_bound = 0;
   (void)s;
 {body}
-  return AMOEBA_OK + AMOEBA_KV_HEAD_MAJOR + AMOEBA_W_DENSE + AMOEBA_T_Q;
+  return AMOEBA_OK + AMOEBA_KV_HEAD_MAJOR + AMOEBA_W_DENSE + AMOEBA_T_Q + AMOEBA_PART_ALL +
+         AMOEBA_TUNE_W_GRID;
 }}
 """
     with tempfile.TemporaryDirectory() as tmp:

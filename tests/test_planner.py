@@ -2,6 +2,7 @@
 header declares, the planner's segment table (interpreted here with numpy)
 reproduces the oracle's shard byte for byte, and bad shapes are rejected."""
 import itertools
+import ctypes
 import os
 import re
 
@@ -22,13 +23,17 @@ def shape_of(m: oracle.Model, **kw) -> ab.ModelShape:
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "amoeba.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(amoeba_[a-z_]+)\s*\(", header))
-    assert declared == set(ab.EXPORTS)
     L = ab.lib()
-    for name in declared:
-        assert hasattr(L, name), name
+    for header, exports in (("amoeba.h", ab.EXPORTS), ("amoeba_measure.h", ab.MEASURE_EXPORTS)):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        declared = set(re.findall(r"\b(amoeba_[a-z_]+)\s*\(", text))
+        assert declared == set(exports), header
+        for name in declared:
+            assert hasattr(L, name), name
+    # the product header stands alone: it neither includes nor mentions the measurement one
+    product = open(os.path.join(ROOT, "include", "amoeba.h")).read()
+    assert "amoeba_measure" not in product and "amoeba_plan_tune" not in product
 
 
 def apply_segments(plan, src_shards, n_layers):
@@ -174,10 +179,16 @@ def test_tune_rejects_unknown_knobs_and_bad_values():
     plan = ab.amoeba_plan(ab.ModelShape(2, 24, 8, 4, 4, 72), 1, 2, 0)
     for knob in range(10):
         ab.amoeba_plan_tune(plan, knob, 0)           # 0 restores the built-in choice
-    for knob, value in [(10, 1), (-1, 1), (ab.TUNE_W_PART, 3), (ab.TUNE_KV_GRID, -5)]:
+    for knob, value in [(10, 1), (-1, 1), (ab.TUNE_KV_SMALL_TABLE, 2), (ab.TUNE_KV_GRID, -5)]:
         with pytest.raises(ab.AmoebaError):
             ab.amoeba_plan_tune(plan, knob, value)
-    assert "AMOEBA_TUNE_W_PART" in ab.amoeba_last_error() or "bad plan or value" in ab.amoeba_last_error()
+    assert "amoeba_plan_tune" in ab.amoeba_last_error()
+    L = ab.lib()
+    buf = (ctypes.c_void_p * 1)()
+    assert L.amoeba_reshard_weights_part(plan.handle, buf, 8, 3, None) == ab.ERR_INVALID_ARG
+    assert "AMOEBA_PART" in ab.amoeba_last_error()
+    with pytest.raises(ab.AmoebaError):
+        ab.amoeba_plan(ab.ModelShape(2, 24, 8, 4, 4, 72, kv_blocks_bound=-1), 1, 2, 0)
 
 
 def test_workload_recipes_are_seeded_and_well_formed():
