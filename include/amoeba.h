@@ -210,9 +210,32 @@ int amoeba_reshard_kv(const amoeba_plan_t* plan, const void* const* src_blocks,
                       const int32_t* src_block_tables, const int32_t* seq_lens, void* dst_blocks,
                       int32_t* dst_block_tables, void* stream);
 
-/* Synchronises `stream`, then returns what the last amoeba_reshard_kv() on this
- * plan found: AMOEBA_OK, AMOEBA_ERR_OVERFLOW or AMOEBA_ERR_BLOCK_ID (AMOEBA_ERR_HIP
- * if the copy back fails).  total_blocks (may be NULL) receives sum_i nb_i. */
+/*
+ * amoeba_reshard_kv() for callers that cannot allocate device memory or let a library do
+ * it: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same result, same kernels, but the kernels' workspace (the status
+ * header, the scanned bases and the new-block -> source-block list) is a static device
+ * array inside the library instead of the plan's allocation, so the call allocates and
+ * frees nothing and calls no allocating routine.  Limits and rules:
+ *   - 8 + num_seqs + dst_pool_blocks must not exceed 2^20 int32 words (the array is
+ *     4 MiB, held by every GPU the library is loaded on until the process ends); beyond
+ *     that the call returns AMOEBA_ERR_INVALID_ARG and amoeba_last_error() says so;
+ *   - every call on one GPU shares that GPU's array, whatever the plan or stream: calls
+ *     that overlap in time on one GPU race, and amoeba_kv_status() reports the last such
+ *     call enqueued on that GPU if it is read after another one was enqueued;
+ *   - the array keeps the last call's contents; nothing needs clearing between calls
+ *     (every word a call reads was written by that call's own kernels first).
+ * The address of the array on a device is looked up when the first plan is created with
+ * that device current (or, failing that, on the first call there).
+ */
+int amoeba_reshard_kv_static(const amoeba_plan_t* plan, const void* const* src_blocks,
+                             const int32_t* src_block_tables, const int32_t* seq_lens,
+                             void* dst_blocks, int32_t* dst_block_tables, void* stream);
+
+/* Synchronises `stream`, then returns what the last amoeba_reshard_kv() (or
+ * amoeba_reshard_kv_static()) enqueued on this plan found: AMOEBA_OK, AMOEBA_ERR_OVERFLOW
+ * or AMOEBA_ERR_BLOCK_ID (AMOEBA_ERR_HIP if the copy back fails).  total_blocks (may be
+ * NULL) receives sum_i nb_i. */
 int amoeba_kv_status(const amoeba_plan_t* plan, void* stream, int64_t* total_blocks);
 
 /*

@@ -35,7 +35,7 @@ MAX_TP = 16
 # every symbol include/amoeba.h declares
 EXPORTS = [
     "amoeba_plan", "amoeba_plan_destroy", "amoeba_reshard_weights", "amoeba_reshard_weights_part",
-    "amoeba_reshard_kv", "amoeba_kv_status", "amoeba_plan_shard_bytes",
+    "amoeba_reshard_kv", "amoeba_reshard_kv_static", "amoeba_kv_status", "amoeba_plan_shard_bytes",
     "amoeba_plan_kv_block_bytes", "amoeba_plan_src_rank_mask", "amoeba_plan_kv_rank_mask",
     "amoeba_plan_tensor_info", "amoeba_plan_kv_stride_order", "amoeba_plan_num_segments",
     "amoeba_plan_segment", "amoeba_last_error", "amoeba_merge_kv_inplace",
@@ -111,6 +111,8 @@ def lib() -> ctypes.CDLL:
     L.amoeba_reshard_weights_part.argtypes = [vp, ctypes.POINTER(vp), vp, i32, vp]
     L.amoeba_reshard_kv.restype = i32
     L.amoeba_reshard_kv.argtypes = [vp, ctypes.POINTER(vp), vp, vp, vp, vp, vp]
+    L.amoeba_reshard_kv_static.restype = i32
+    L.amoeba_reshard_kv_static.argtypes = [vp, ctypes.POINTER(vp), vp, vp, vp, vp, vp]
     L.amoeba_kv_status.restype = i32
     L.amoeba_kv_status.argtypes = [vp, vp, ctypes.POINTER(i64)]
     L.amoeba_plan_shard_bytes.restype = ctypes.c_size_t
@@ -243,6 +245,16 @@ def amoeba_reshard_kv(plan: Plan, src_blocks, src_block_tables, seq_lens, dst_bl
     rc = lib().amoeba_reshard_kv(plan.handle, _ptr_array(src_blocks, plan.src_tp),
                                  _ptr(src_block_tables), _ptr(seq_lens), _ptr(dst_blocks),
                                  _ptr(dst_block_tables), _stream_handle(stream))
+    if check and rc != OK:
+        raise AmoebaError(rc, amoeba_last_error())
+    return rc
+
+
+def amoeba_reshard_kv_static(plan: Plan, src_blocks, src_block_tables, seq_lens, dst_blocks,
+                             dst_block_tables, stream=None, check: bool = True) -> int:
+    rc = lib().amoeba_reshard_kv_static(plan.handle, _ptr_array(src_blocks, plan.src_tp),
+                                        _ptr(src_block_tables), _ptr(seq_lens), _ptr(dst_blocks),
+                                        _ptr(dst_block_tables), _stream_handle(stream))
     if check and rc != OK:
         raise AmoebaError(rc, amoeba_last_error())
     return rc

@@ -89,6 +89,11 @@ amoeba_plan_t* amoeba_plan(const amoeba_model_shape* shape, int src_tp, int dst_
         delete p;
         return nullptr;
       }
+      // set-up time is when the static workspace's address on this device is looked up (the
+      // first lookup may load the code object), so that amoeba_reshard_kv_static() itself
+      // finds it cached; a failure is reported by that call, not here
+      std::string ignored;
+      (void)amoeba::static_kv_workspace(&ignored);
       p->device = dev;
       p->workspace = static_cast<int32_t*>(ws);
       p->workspace_bytes = bytes;
@@ -168,6 +173,36 @@ int amoeba_reshard_kv(const amoeba_plan_t* plan, const void* const* src_blocks,
                                            static_cast<hipStream_t>(stream), &err);
   if (rc != AMOEBA_OK) set_error("amoeba_reshard_kv: " + err);
   else plan->status_ws = plan->workspace;
+  return rc;
+}
+
+int amoeba_reshard_kv_static(const amoeba_plan_t* plan, const void* const* src_blocks,
+                             const int32_t* src_block_tables, const int32_t* seq_lens,
+                             void* dst_blocks, int32_t* dst_block_tables, void* stream) {
+  if (!plan || !src_blocks) {
+    set_error("amoeba_reshard_kv_static: NULL plan or src_blocks");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  const uint64_t need = uint64_t(amoeba::kWsHeader) + uint64_t(plan->shape.num_seqs) +
+                        uint64_t(plan->shape.dst_pool_blocks);
+  if (need > amoeba::static_kv_workspace_ints()) {
+    set_error("amoeba_reshard_kv_static: 8 + num_seqs + dst_pool_blocks = " +
+              std::to_string(need) + " int32 words exceed the static workspace of " +
+              std::to_string(amoeba::static_kv_workspace_ints()) +
+              " words; use amoeba_reshard_kv()");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  std::string err;
+  int32_t* ws = amoeba::static_kv_workspace(&err);
+  if (!ws) {
+    set_error("amoeba_reshard_kv_static: " + err);
+    return AMOEBA_ERR_HIP;
+  }
+  const int rc = amoeba::launch_reshard_kv(plan, ws, src_blocks, src_block_tables, seq_lens,
+                                           dst_blocks, dst_block_tables,
+                                           static_cast<hipStream_t>(stream), &err);
+  if (rc != AMOEBA_OK) set_error("amoeba_reshard_kv_static: " + err);
+  else plan->status_ws = ws;
   return rc;
 }
 

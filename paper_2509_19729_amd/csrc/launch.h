@@ -25,6 +25,11 @@ int launch_reshard_kv(const amoeba_plan_s* p, int32_t* ws, const void* const* sr
                       const int32_t* src_block_tables, const int32_t* seq_lens, void* dst_blocks,
                       int32_t* dst_block_tables, hipStream_t stream, std::string* err);
 
+// The static workspace of amoeba_reshard_kv_static(): its address on the current device
+// (nullptr and a message on failure; the first call on a device looks it up) and its size.
+int32_t* static_kv_workspace(std::string* err);
+size_t static_kv_workspace_ints();
+
 // Launch geometry of the three copy kernels for pointers aligned to align_bytes (host only).
 bool weights_launch_geometry(const amoeba_plan_s* p, int align_bytes, LaunchShape* out,
                              std::string* err);

@@ -29,12 +29,49 @@
 #include <algorithm>
 #include <string>
 
+#include <mutex>
+
 #include "device_common.h"
 #include "grid.h"
 #include "launch.h"
 #include "plan.h"
 
+// Workspace of amoeba_reshard_kv_static(), for callers that cannot allocate: 4 MiB of
+// device memory that every GPU the library runs on holds from the moment the code object
+// is loaded there until the process ends.  This name is a host-side stand-in, not a device
+// address: host code only ever uses the address static_kv_workspace() looks up.
+constexpr size_t kScratchInts = size_t(1) << 20;
+static __device__ __align__(256) int32_t scratch[kScratchInts];
+
 namespace amoeba {
+
+size_t static_kv_workspace_ints() { return kScratchInts; }
+
+// Device address of `scratch` on the current device, looked up once per device (each GPU has
+// its own copy of the array at its own address).  nullptr and a message on failure.
+int32_t* static_kv_workspace(std::string* err) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static int32_t* ptr[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t rc = hipGetDevice(&dev);
+  if (rc != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    *err = rc != hipSuccess ? std::string("hipGetDevice: ") + hipGetErrorString(rc)
+                            : std::string("device index outside [0, 64)");
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    rc = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (rc != hipSuccess || !p) {
+      *err = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(rc);
+      return nullptr;
+    }
+    ptr[dev] = static_cast<int32_t*>(p);
+  }
+  return ptr[dev];
+}
 
 constexpr int kScanThreads = 1024;
 constexpr int kScanWaves = kScanThreads / 64;
