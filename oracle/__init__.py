@@ -145,6 +145,13 @@ def lib():
                                           ctypes.POINTER(ctypes.c_void_p),
                                           ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p,
                                           ctypes.POINTER(ctypes.c_int64)]
+        L.ao_merge_kv_base.restype = ctypes.c_int
+        L.ao_merge_kv_base.argtypes = [ctypes.POINTER(_KV), ctypes.c_int, ctypes.c_int,
+                                       ctypes.c_int, ctypes.POINTER(ctypes.c_void_p),
+                                       ctypes.POINTER(ctypes.c_void_p),
+                                       ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p,
+                                       ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64),
+                                       ctypes.POINTER(ctypes.c_int64)]
         L.ao_padded_shard_elems.restype = ctypes.c_int64
         L.ao_padded_shard_elems.argtypes = [ctypes.POINTER(_Model), ctypes.POINTER(_Pad),
                                             ctypes.c_int]
@@ -248,6 +255,27 @@ def merge_kv_inplace(c: KV, src_tp: int, m: int, dst_rank: int, local_pool, remo
                                    local_pool.ctypes.data, pools, tptr, lptr,
                                    dst_table.ctypes.data, ctypes.byref(n))
     return int(st), dst_table, int(n.value)
+
+
+def merge_kv_base(c: KV, src_tp: int, m: int, dst_rank: int, pools, src_tables, seq_lens,
+                  new_pool, dst_table=None):
+    """The base solution of Sec. 3.1 (migration, then de-fragmentation, into new_pool, which is
+    written in place).  pools: m arrays [kv_layers, P, block(src_tp)]; src_tables, seq_lens:
+    m arrays each.  Returns (status, dst_table [m*S, W], migrated_blocks, defrag_blocks)."""
+    dt = elem_dtype(c.elem_bytes)
+    assert new_pool.dtype == dt and new_pool.flags["C_CONTIGUOUS"]
+    tabs = [np.ascontiguousarray(t, dtype=np.int32) for t in src_tables]
+    lens = [np.ascontiguousarray(x, dtype=np.int32) for x in seq_lens]
+    if dst_table is None:
+        dst_table = np.full((m * c.num_seqs, c.max_blocks_per_seq), -7, dtype=np.int32)
+    pptr, _k1 = _ptr_array(pools, max(m, 1), dt)
+    tptr, _k2 = _ptr_array(tabs, max(m, 1), np.int32)
+    lptr, _k3 = _ptr_array(lens, max(m, 1), np.int32)
+    mig, dfr = ctypes.c_int64(-1), ctypes.c_int64(-1)
+    st = lib().ao_merge_kv_base(ctypes.byref(c._c()), src_tp, m, dst_rank, pptr, tptr, lptr,
+                                new_pool.ctypes.data, dst_table.ctypes.data, ctypes.byref(mig),
+                                ctypes.byref(dfr))
+    return int(st), dst_table, int(mig.value), int(dfr.value)
 
 
 def padded_shard_elems(m: Model, pad: Pad, tp: int) -> int:

@@ -259,6 +259,88 @@ int merge_kv_inplace_t(const ao_kv* c, int k, int m, int rp, void* local_v,
   return bad_id ? AO_ERR_BLOCK_ID : AO_OK;
 }
 
+// ---- base solution of Sec. 3.1: migration, then de-fragmentation ---------------------------
+//
+// m instances at TP=k become one at TP=k*m without the in-place trick.  The worker that hosted
+// rank s of instance g becomes rank r' = s*m + g.  It gets a second pool ("reserved pages" for
+// what it receives, plus room for its own cache in compact form) and two passes fill it:
+//   migration        for every request of every OTHER instance, the heads of r' are taken
+//                    out of the sender's blocks and stored in reserved blocks;
+//   de-fragmentation for every LOCAL request, the heads r' keeps are taken out of the old
+//                    blocks (where they sit between the heads that were given away) and
+//                    stored compactly; afterwards the old pool can be released.
+// New ids are compact over the merged sequence list in instance-major order, so the table is
+// the same on every worker and instance g2's blocks are the id range starting at the number
+// of blocks of instances 0 .. g2-1.
+template <typename E>
+int merge_kv_base_t(const ao_kv* c, int k, int m, int rp, const void* const* pools_v,
+                    const int32_t* const* tables, const int32_t* const* lens, void* new_pool_v,
+                    int32_t* dst_table, int64_t* migrated_out, int64_t* defrag_out) {
+  const int64_t S = c->num_seqs, W = c->max_blocks_per_seq, B = c->block_tokens, d = c->head_dim;
+  const int64_t P = c->src_pool_blocks, Pn = c->dst_pool_blocks;
+  const int64_t g = rp % m;                          // the instance hosted here
+  const int64_t Hs = c->n_kv_heads / k;              // heads in an old block
+  const int64_t Hd = c->n_kv_heads / ((int64_t)k * m);  // heads in a new block
+  const int64_t old_block = Hs * 2 * B * d, new_block = Hd * 2 * B * d;
+  if (migrated_out) *migrated_out = 0;
+  if (defrag_out) *defrag_out = 0;
+  for (int64_t i = 0; i < (int64_t)m * S * W; ++i) dst_table[i] = -1;
+
+  // blocks per sequence, checks, compact ids
+  int64_t total = 0;
+  bool overflow = false;
+  for (int64_t g2 = 0; g2 < m; ++g2)
+    for (int64_t i = 0; i < S; ++i) {
+      const int64_t len = lens[g2][i];
+      if (len < 0) { overflow = true; continue; }
+      const int64_t nb = (len + B - 1) / B;
+      if (nb > W) overflow = true;
+      total += nb;
+    }
+  if (total > Pn) overflow = true;
+  if (overflow) return AO_ERR_OVERFLOW;
+  int64_t next = 0;
+  for (int64_t g2 = 0; g2 < m; ++g2)
+    for (int64_t i = 0; i < S; ++i) {
+      const int64_t nb = ((int64_t)lens[g2][i] + B - 1) / B;
+      for (int64_t j = 0; j < nb; ++j) dst_table[(g2 * S + i) * W + j] = (int32_t)next++;
+    }
+
+  E* fresh = static_cast<E*>(new_pool_v);
+  bool bad_id = false;
+  // heads [g*Hd, (g+1)*Hd) of the old block are the ones rank r' owns: its global range
+  // [r'*Hd, (r'+1)*Hd) starts at s*Hs + g*Hd and rank s's block starts at head s*Hs
+  auto move_heads = [&](int64_t g2, int64_t* count) {
+    const E* pool = static_cast<const E*>(pools_v[g2]);
+    for (int64_t i = 0; i < S; ++i) {
+      const int64_t nb = ((int64_t)lens[g2][i] + B - 1) / B;
+      for (int64_t j = 0; j < nb; ++j) {
+        const int64_t sb = tables[g2][i * W + j];
+        const int64_t db = dst_table[(g2 * S + i) * W + j];
+        if (sb < 0 || sb >= P) { bad_id = true; continue; }
+        ++*count;
+        for (int64_t l = 0; l < c->kv_layers; ++l) {
+          const E* from = pool + (l * P + sb) * old_block;
+          E* to = fresh + (l * Pn + db) * new_block;
+          for (int64_t t = 0; t < B; ++t)
+            for (int64_t kv = 0; kv < 2; ++kv)
+              for (int64_t hp = 0; hp < Hd; ++hp)
+                for (int64_t x = 0; x < d; ++x)
+                  to[block_index(c->layout_dst, hp, kv, t, x, Hd, B, d)] =
+                      from[block_index(c->layout_src, g * Hd + hp, kv, t, x, Hs, B, d)];
+        }
+      }
+    }
+  };
+  int64_t migrated = 0, defragged = 0;
+  for (int64_t g2 = 0; g2 < m; ++g2)  // pass 1: migration of the remote requests
+    if (g2 != g) move_heads(g2, &migrated);
+  move_heads(g, &defragged);          // pass 2: de-fragmentation of the local requests
+  if (migrated_out) *migrated_out = migrated;
+  if (defrag_out) *defrag_out = defragged;
+  return bad_id ? AO_ERR_BLOCK_ID : AO_OK;
+}
+
 // ---- padded, partition-major FFN layout (Sec. 3.2, Improvement 1) ---------------------
 //
 // T = pad->max_tp is the finest TP degree of the model's TP set.  Every FFN tensor is cut in
@@ -525,6 +607,29 @@ int ao_merge_kv_inplace(const ao_kv* c, int src_tp, int m, int dst_rank, void* l
     default:
       return merge_kv_inplace_t<uint32_t>(c, src_tp, m, dst_rank, local_pool, remote_pools,
                                           src_tables, seq_lens, dst_table, remote_blocks_out);
+  }
+}
+
+int ao_merge_kv_base(const ao_kv* c, int src_tp, int m, int dst_rank, const void* const* pools,
+                     const int32_t* const* src_tables, const int32_t* const* seq_lens,
+                     void* new_pool, int32_t* dst_table, int64_t* migrated_blocks_out,
+                     int64_t* defrag_blocks_out) {
+  if (!kv_ok(c) || m < 2 || m > 64 || src_tp < 1 || !divides(src_tp * m, c->n_kv_heads) ||
+      dst_rank < 0 || dst_rank >= src_tp * m || !pools || !src_tables || !seq_lens ||
+      !dst_table || (!new_pool && c->dst_pool_blocks > 0))
+    return AO_ERR_ARG;
+  for (int g2 = 0; g2 < m; ++g2)
+    if (!src_tables[g2] || !seq_lens[g2] || !pools[g2]) return AO_ERR_ARG;
+  switch (c->elem_bytes) {
+    case 1:
+      return merge_kv_base_t<uint8_t>(c, src_tp, m, dst_rank, pools, src_tables, seq_lens,
+                                      new_pool, dst_table, migrated_blocks_out, defrag_blocks_out);
+    case 2:
+      return merge_kv_base_t<uint16_t>(c, src_tp, m, dst_rank, pools, src_tables, seq_lens,
+                                       new_pool, dst_table, migrated_blocks_out, defrag_blocks_out);
+    default:
+      return merge_kv_base_t<uint32_t>(c, src_tp, m, dst_rank, pools, src_tables, seq_lens,
+                                       new_pool, dst_table, migrated_blocks_out, defrag_blocks_out);
   }
 }
 

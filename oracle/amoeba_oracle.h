@@ -122,6 +122,28 @@ int ao_merge_kv_inplace(const ao_kv* c, int src_tp, int m, int dst_rank, void* l
                         const int32_t* const* seq_lens, int32_t* dst_table,
                         int64_t* remote_blocks_out);
 
+/* The base solution of Sec. 3.1 for the same merge of m instances (TP=src_tp each) into one
+ * at TP=src_tp*m: migration, then de-fragmentation, into a second pool.  Target rank
+ * r' = s*m + g is hosted where rank s of instance g was.  pools[g2] is the pool of rank s of
+ * instance g2, [kv_layers][P][block(src_tp)] in c->layout_src (all m entries are read; entry g
+ * is the worker's own).  new_pool is [kv_layers][c->dst_pool_blocks][block(src_tp*m)] in
+ * c->layout_dst: the reserved pages for what the worker receives plus room for its own
+ * requests in compact form; the paper's base solution stores both sides token-first.
+ *   pass 1 (migration): for every request of every other instance, the heads r' owns are
+ *     taken out of the sender's blocks and stored in new blocks;
+ *   pass 2 (de-fragmentation): for every local request the heads r' keeps, which sit between
+ *     the heads it gave away, are stored compactly in new blocks.
+ * New ids are compact over the merged sequence list, instance-major (exclusive prefix sum of
+ * ceil(len / block_tokens)); dst_table is [m*num_seqs][max_blocks_per_seq], -1 padded, the
+ * same for every target rank.  Negative length, short row or sum of blocks > dst_pool_blocks:
+ * AO_ERR_OVERFLOW, nothing written, table all -1.  An id outside [0, P): that block is skipped
+ * (its new block keeps its bytes), AO_ERR_BLOCK_ID.  migrated_blocks_out / defrag_blocks_out
+ * (may be NULL): blocks moved by either pass, per layer. */
+int ao_merge_kv_base(const ao_kv* c, int src_tp, int m, int dst_rank, const void* const* pools,
+                     const int32_t* const* src_tables, const int32_t* const* seq_lens,
+                     void* new_pool, int32_t* dst_table, int64_t* migrated_blocks_out,
+                     int64_t* defrag_blocks_out);
+
 /* Padded, partition-major FFN layout (Sec. 3.2, Improvement 1: padding at every potential
  * TP boundary so that each partition starts on an allocation granule and a split only has
  * to release pages).  max_tp = finest TP degree T; every FFN tensor is cut in T partitions;
