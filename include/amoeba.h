@@ -40,15 +40,16 @@
  * amoeba_plan().  The plan owns two device workspaces, allocated once by
  * amoeba_plan() and freed by amoeba_plan_destroy(); the reshard calls themselves
  * never allocate, free or synchronise:
- *   - for amoeba_reshard_kv(): 4 * (8 + num_seqs + dst_pool_blocks) bytes (a status
+ *   - for amoeba_reshard_kv() and amoeba_merge_kv_base(): 4 * (8 + m * num_seqs +
+ *     dst_pool_blocks) bytes, m = dst_tp / src_tp if that is an integer, else 1 (a status
  *     header, the scanned base of every sequence, and the source id of every new
  *     block, which the block-regroup kernel reads instead of searching the table);
  *   - for amoeba_merge_kv_inplace(), when the plan qualifies: about
  *     8 * m * src_pool_blocks bytes (a flag and a work-list entry per new block id).
  * The kernels of a call write these, so two amoeba_reshard_kv() calls (or two
- * amoeba_merge_kv_inplace() calls) on the same plan must not overlap in time; use
- * one plan per stream.  amoeba_reshard_weights() uses no workspace and its calls
- * may overlap freely.
+ * amoeba_merge_kv_inplace() or amoeba_merge_kv_base() calls) on the same plan must not
+ * overlap in time; use one plan per stream.  amoeba_reshard_weights() uses no workspace
+ * and its calls may overlap freely.
  */
 #ifndef AMOEBA_H
 #define AMOEBA_H
@@ -271,6 +272,37 @@ int amoeba_merge_kv_inplace(const amoeba_plan_t* plan, void* local_pool,
                             const int32_t* const* src_block_tables,
                             const int32_t* const* seq_lens, int32_t* dst_block_tables,
                             void* stream);
+
+/*
+ * The same merge of m = dst_tp / src_tp instances the base way (Sec. 3.1, base solution:
+ * migration and de-fragmentation), for comparison with the in-place merge and for engines
+ * whose blocks are token-first.  The worker gets a second pool; two passes fill it:
+ *   migration       : for every request of every other instance, the heads dst_rank owns
+ *                     are taken out of the sender's blocks and stored in new blocks (the
+ *                     reserved pages of the paper);
+ *   de-fragmentation: for every local request, the heads dst_rank keeps (which sit between
+ *                     the heads it gave away) are stored compactly in new blocks; the old
+ *                     pool can be released afterwards.
+ *   pools            : HOST array of m DEVICE pointers, entry g2 = pool of rank s of instance
+ *                      g2, [kv_layers][src_pool_blocks][block(src_tp)] in kv_layout_src, read
+ *                      only (dst_rank = s*m + g; entry g is the worker's own pool).
+ *   src_block_tables : HOST array of m DEVICE int32 [num_seqs][max_blocks_per_seq].
+ *   seq_lens         : HOST array of m DEVICE int32 [num_seqs].
+ *   new_pool         : DEVICE [kv_layers][dst_pool_blocks][block(dst_tp)] in kv_layout_dst;
+ *                      must not overlap any source pool.
+ *   dst_block_tables : DEVICE int32 [m*num_seqs][max_blocks_per_seq], instance-major: compact
+ *                      ids over the merged sequence list (exclusive prefix sum of
+ *                      ceil(len / kv_block_tokens)), -1 padded; identical for every dst_rank.
+ * Any layout pair works (the paper's base solution is token-first on both sides).  Enqueues
+ * four kernels (scan, table, one block gather per pass), no host synchronisation, no memory
+ * beyond the plan's workspace (4 * (8 + m*num_seqs + dst_pool_blocks) bytes) and new_pool
+ * itself.  kv_blocks_bound bounds the blocks of all instances together.  Device-found
+ * conditions are read with amoeba_kv_status() (total_blocks = blocks of all instances) and
+ * are those of amoeba_reshard_kv().  Calls on one plan must not overlap in time.
+ */
+int amoeba_merge_kv_base(const amoeba_plan_t* plan, const void* const* pools,
+                         const int32_t* const* src_block_tables, const int32_t* const* seq_lens,
+                         void* new_pool, int32_t* dst_block_tables, void* stream);
 
 /* Like amoeba_kv_status() for the last amoeba_merge_kv_inplace() on this plan;
  * remote_blocks (may be NULL) receives the blocks copied per layer. */

@@ -38,7 +38,7 @@ EXPORTS = [
     "amoeba_reshard_kv", "amoeba_reshard_kv_static", "amoeba_kv_status", "amoeba_plan_shard_bytes",
     "amoeba_plan_kv_block_bytes", "amoeba_plan_src_rank_mask", "amoeba_plan_kv_rank_mask",
     "amoeba_plan_tensor_info", "amoeba_plan_kv_stride_order", "amoeba_plan_num_segments",
-    "amoeba_plan_segment", "amoeba_last_error", "amoeba_merge_kv_inplace",
+    "amoeba_plan_segment", "amoeba_last_error", "amoeba_merge_kv_inplace", "amoeba_merge_kv_base",
     "amoeba_merge_kv_status", "amoeba_plan_merge_factor", "amoeba_plan_padded_info",
     "amoeba_plan_ffn_view", "amoeba_plan_expert_info",
 ]
@@ -140,6 +140,9 @@ def lib() -> ctypes.CDLL:
     L.amoeba_merge_kv_inplace.restype = i32
     L.amoeba_merge_kv_inplace.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                           ctypes.POINTER(vp), vp, vp]
+    L.amoeba_merge_kv_base.restype = i32
+    L.amoeba_merge_kv_base.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                       ctypes.POINTER(vp), vp, vp, vp]
     L.amoeba_merge_kv_status.restype = i32
     L.amoeba_merge_kv_status.argtypes = [vp, vp, ctypes.POINTER(i64)]
     L.amoeba_plan_merge_factor.restype = i32
@@ -347,6 +350,17 @@ def amoeba_merge_kv_inplace(plan: Plan, local_pool, remote_pools, src_block_tabl
     rc = lib().amoeba_merge_kv_inplace(plan.handle, _ptr(local_pool), _ptr_array(remote_pools, m),
                                        _ptr_array(src_block_tables, m), _ptr_array(seq_lens, m),
                                        _ptr(dst_block_tables), _stream_handle(stream))
+    if check and rc != OK:
+        raise AmoebaError(rc, amoeba_last_error())
+    return rc
+
+
+def amoeba_merge_kv_base(plan: Plan, pools, src_block_tables, seq_lens, new_pool,
+                         dst_block_tables, stream=None, check: bool = True) -> int:
+    m = max(plan.dst_tp // max(plan.src_tp, 1), 1)
+    rc = lib().amoeba_merge_kv_base(plan.handle, _ptr_array(pools, m),
+                                    _ptr_array(src_block_tables, m), _ptr_array(seq_lens, m),
+                                    _ptr(new_pool), _ptr(dst_block_tables), _stream_handle(stream))
     if check and rc != OK:
         raise AmoebaError(rc, amoeba_last_error())
     return rc

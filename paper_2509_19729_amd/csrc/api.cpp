@@ -79,7 +79,10 @@ amoeba_plan_t* amoeba_plan(const amoeba_model_shape* shape, int src_tp, int dst_
       int cu = 0;
       if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
         p->n_cu = cu;
-      const size_t bytes = sizeof(int32_t) * (size_t(amoeba::kWsHeader) + size_t(p->shape.num_seqs) +
+      // a merge of m = dst_tp / src_tp instances scans m * num_seqs sequences
+      const size_t inst = (p->kp % p->k == 0 && p->kp > p->k) ? size_t(p->kp / p->k) : 1;
+      const size_t bytes = sizeof(int32_t) * (size_t(amoeba::kWsHeader) +
+                                              inst * size_t(p->shape.num_seqs) +
                                               size_t(p->shape.dst_pool_blocks));
       void* ws = nullptr;
       const hipError_t rc = hipMalloc(&ws, bytes);
@@ -228,6 +231,32 @@ int amoeba_merge_kv_inplace(const amoeba_plan_t* plan, void* local_pool,
                                                  seq_lens, dst_block_tables,
                                                  static_cast<hipStream_t>(stream), &err);
   if (rc != AMOEBA_OK) set_error("amoeba_merge_kv_inplace: " + err);
+  return rc;
+}
+
+int amoeba_merge_kv_base(const amoeba_plan_t* plan, const void* const* pools,
+                         const int32_t* const* src_block_tables, const int32_t* const* seq_lens,
+                         void* new_pool, int32_t* dst_block_tables, void* stream) {
+  if (!plan) {
+    set_error("amoeba_merge_kv_base: NULL plan");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  if (!plan->workspace) {
+    set_error("amoeba_merge_kv_base: the plan has no device workspace (it was created without a GPU)");
+    return AMOEBA_ERR_HIP;
+  }
+  int current_device = -1;
+  if (hipGetDevice(&current_device) != hipSuccess || current_device != plan->device) {
+    set_error("amoeba_merge_kv_base: the current device is not the one the plan's workspace was "
+              "allocated on");
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  std::string err;
+  const int rc = amoeba::launch_merge_kv_base(plan, plan->workspace, pools, src_block_tables,
+                                              seq_lens, new_pool, dst_block_tables,
+                                              static_cast<hipStream_t>(stream), &err);
+  if (rc != AMOEBA_OK) set_error("amoeba_merge_kv_base: " + err);
+  else plan->status_ws = plan->workspace;
   return rc;
 }
 

@@ -12,7 +12,7 @@ struct amoeba_plan_s;
 namespace amoeba {
 
 // Workspace header (int32 words) shared by the KV kernels and the status call.
-enum { kWsTotal = 0, kWsError = 1, kWsHeader = 8 };
+enum { kWsTotal = 0, kWsError = 1, kWsLocalBase = 2, kWsLocalCount = 3, kWsHeader = 8 };
 enum { kErrNegativeLen = 1, kErrRowTooShort = 2, kErrPoolTooSmall = 4, kErrBlockId = 8 };
 
 // part: AMOEBA_PART_ALL, _ATTENTION or _FFN.
@@ -29,6 +29,13 @@ int launch_reshard_kv(const amoeba_plan_s* p, int32_t* ws, const void* const* sr
 // (nullptr and a message on failure; the first call on a device looks it up) and its size.
 int32_t* static_kv_workspace(std::string* err);
 size_t static_kv_workspace_ints();
+
+// Base solution of Sec. 3.1 (migration pass, de-fragmentation pass) for m = dst_tp / src_tp
+// instances; ws: 8 + m * num_seqs + dst_pool_blocks int32 words.
+int launch_merge_kv_base(const amoeba_plan_s* p, int32_t* ws, const void* const* pools,
+                         const int32_t* const* src_block_tables, const int32_t* const* seq_lens,
+                         void* new_pool, int32_t* dst_block_tables, hipStream_t stream,
+                         std::string* err);
 
 // Launch geometry of the three copy kernels for pointers aligned to align_bytes (host only).
 bool weights_launch_geometry(const amoeba_plan_s* p, int align_bytes, LaunchShape* out,

@@ -76,13 +76,25 @@ int32_t* static_kv_workspace(std::string* err) {
 constexpr int kScanThreads = 1024;
 constexpr int kScanWaves = kScanThreads / 64;
 
+// Lengths and tables of the sequences a call works on: one instance for the reshard, m
+// instances (instance-major) for the merge of Sec. 3.1.  Sequence q of the merged list is
+// sequence q mod seqs of instance q / seqs.
+struct SeqInputs {
+  const int32_t* lens[AMOEBA_MAX_TP];
+  const int32_t* tables[AMOEBA_MAX_TP];
+  FastDiv seqs;         // sequences per instance
+  uint32_t n_inst;      // instances (1: a plain reshard)
+  uint32_t local_inst;  // the instance hosted where the target rank is (merge only)
+};
+
 __global__ void __launch_bounds__(kScanThreads)
-kv_scan_kernel(const int32_t* __restrict__ seq_lens, uint32_t num_seqs, uint32_t row_width,
-               uint32_t block_tokens, int64_t dst_pool_blocks, int32_t* __restrict__ ws) {
+kv_scan_kernel(const SeqInputs in, uint32_t row_width, uint32_t block_tokens,
+               int64_t dst_pool_blocks, int32_t* __restrict__ ws) {
   __shared__ long long wave_total[kScanWaves];
   __shared__ long long carry_s;
   __shared__ unsigned int err_s;
   const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint32_t num_seqs = in.n_inst * in.seqs.d;
   int32_t* base = ws + kWsHeader;
   if (tid == 0) { carry_s = 0; err_s = 0; }
   __syncthreads();
@@ -92,7 +104,8 @@ kv_scan_kernel(const int32_t* __restrict__ seq_lens, uint32_t num_seqs, uint32_t
     long long nb = 0;
     unsigned int e = 0;
     if (i < num_seqs) {
-      const long long len = seq_lens[i];
+      const uint32_t inst = fd_div(i, in.seqs);
+      const long long len = in.lens[inst][i - inst * in.seqs.d];
       if (len < 0) {
         e = kErrNegativeLen;
       } else {
@@ -131,29 +144,46 @@ kv_scan_kernel(const int32_t* __restrict__ seq_lens, uint32_t num_seqs, uint32_t
     if (total > dst_pool_blocks) e |= kErrPoolTooSmall;
     ws[kWsTotal] = e ? 0 : (int32_t)total;
     ws[kWsError] = (int32_t)e;
+    // the id range of the local instance's blocks (the bases were written by this workgroup
+    // before the barriers above)
+    int32_t lo = 0, n = 0;
+    if (!e && in.n_inst > 1 && in.seqs.d > 0) {
+      lo = base[in.local_inst * in.seqs.d];
+      const int32_t hi = in.local_inst + 1 < in.n_inst ? base[(in.local_inst + 1) * in.seqs.d]
+                                                        : (int32_t)total;
+      n = hi - lo;
+    }
+    ws[kWsLocalBase] = lo;
+    ws[kWsLocalCount] = n;
   }
 }
 
+// One lane per cell of the (merged) table: the new id of the cell's block, and the flat list
+// new id -> source block id (for a merge: source id * instances + instance).
 __global__ void __launch_bounds__(kThreads)
-kv_table_kernel(const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ src_table,
-                int32_t* __restrict__ dst_table, uint32_t num_seqs, FastDiv row_width,
+kv_table_kernel(const SeqInputs in, int32_t* __restrict__ dst_table, FastDiv row_width,
                 uint32_t block_tokens, int64_t src_pool_blocks, int32_t* __restrict__ ws) {
+  const uint32_t num_seqs = in.n_inst * in.seqs.d;
   const uint64_t cell = uint64_t(blockIdx.x) * kThreads + threadIdx.x;
   const uint64_t cells = uint64_t(num_seqs) * row_width.d;
   if (cell >= cells) return;
-  const uint32_t i = fd_div(uint32_t(cell), row_width);  // cells < 2^32 is checked on the host
-  const uint32_t j = uint32_t(cell) - i * row_width.d;
+  const uint32_t q = fd_div(uint32_t(cell), row_width);  // cells < 2^32 is checked on the host
+  const uint32_t j = uint32_t(cell) - q * row_width.d;
+  const uint32_t inst = fd_div(q, in.seqs);
+  const uint32_t i = q - inst * in.seqs.d;
   const bool failed = (ws[kWsError] & (kErrNegativeLen | kErrRowTooShort | kErrPoolTooSmall)) != 0;
   int32_t out = -1;
   if (!failed) {
-    const long long len = seq_lens[i];
+    const long long len = in.lens[inst][i];
     const long long nb = (len + block_tokens - 1) / block_tokens;
     if ((long long)j < nb) {
-      out = ws[kWsHeader + i] + (int32_t)j;
-      int32_t sb = src_table[cell];
+      out = ws[kWsHeader + q] + (int32_t)j;
+      int32_t sb = in.tables[inst][uint64_t(i) * row_width.d + j];
       if (sb < 0 || (int64_t)sb >= src_pool_blocks) {
         atomicOr(reinterpret_cast<unsigned int*>(ws + kWsError), (unsigned int)kErrBlockId);
         sb = -1;
+      } else if (in.n_inst > 1) {
+        sb = sb * (int32_t)in.n_inst + (int32_t)inst;  // < 2^31, checked on the host
       }
       ws[kWsHeader + num_seqs + out] = sb;
     }
@@ -179,6 +209,11 @@ struct KVArgs {
   FastDiv heads_dst;         // heads per target rank
   FastDiv head_vecs;         // vectors of one head in a header-centric block: 2 * B * dv
   FastDiv dv;                // vectors of one head vector (d * elem_bytes / VEC)
+  // merge of m instances (base solution of Sec. 3.1); n_inst.d <= 1: a plain reshard
+  FastDiv n_inst;            // m: a work-list entry is source id * m + instance, src[] holds
+                             // the instances' pools and head0 is relative to the old block
+  uint32_t pass;             // 0: migration (blocks of the other instances), 1: de-fragmentation
+                             // (blocks of the local instance)
 };
 
 // Moves one tile (THREADS * UNROLL vectors, contiguous in the destination block) of new
@@ -188,7 +223,8 @@ struct KVArgs {
 // layout; all loads of the tile are issued before its stores.
 template <int SL, int DL, int VEC, int THREADS, int UNROLL, bool NT>
 __device__ __forceinline__ void regroup_tile(const KVArgs& a, uint32_t layer, uint32_t b,
-                                             uint32_t tile, int32_t sb, uint32_t tid) {
+                                             uint32_t tile, int32_t sb, uint32_t tid,
+                                             const char* one_pool = nullptr) {
   using V = typename VecOf<VEC>::type;
   constexpr uint32_t kTileVecs = THREADS * UNROLL;
   const char* sp[UNROLL];
@@ -224,7 +260,9 @@ __device__ __forceinline__ void regroup_tile(const KVArgs& a, uint32_t layer, ui
     // rank; then the choice is a select between two scalar-loaded pointers and
     // costs no memory access.
     const char* pool;
-    if (a.n_src <= 2)
+    if (one_pool)  // merge: every head of the block comes from the block's instance
+      pool = one_pool;
+    else if (a.n_src <= 2)
       pool = (s == a.rank_lo) ? a.src_lo : a.src_hi;
     else
       pool = a.src[live[u] ? s : a.rank_lo];  // s < src_tp on live lanes
@@ -252,7 +290,14 @@ kv_regroup_kernel(const KVArgs a, const int32_t* __restrict__ ws) {
   const uint32_t layer = blockIdx.y;
   const uint32_t total = (uint32_t)ws[kWsTotal];
   const int32_t* __restrict__ worklist = ws + kWsHeader + a.num_seqs;
-  const uint32_t n_items = total * a.tiles_per_block.d;  // < 2^32, bounded on the host
+  // A merge runs this kernel twice: the migration pass takes the blocks outside the local
+  // instance's id range [local_base, local_base + local_n), the de-fragmentation pass the
+  // ones inside.  (All of this is uniform: scalar loads and scalar arithmetic.)
+  const bool merge = a.n_inst.d > 1;
+  const uint32_t local_base = merge ? (uint32_t)ws[kWsLocalBase] : 0u;
+  const uint32_t local_n = merge ? (uint32_t)ws[kWsLocalCount] : 0u;
+  const uint32_t n_blocks = !merge ? total : (a.pass ? local_n : total - local_n);
+  const uint32_t n_items = n_blocks * a.tiles_per_block.d;  // < 2^32, bounded on the host
   // Items are taken in the XCD-chunked order (see xcd_item()): +4 % for workgroups of four
   // wavefronts, +1-2 % for single-wavefront ones on the block gather (a plain copy with
   // single-wavefront workgroups does not gain from it).
@@ -261,10 +306,18 @@ kv_regroup_kernel(const KVArgs a, const int32_t* __restrict__ ws) {
   for (uint32_t wi = blockIdx.x; wi < n_loop; wi += gridDim.x) {
     const uint32_t w = xcd_item(wi, n_items);
     if (w >= n_items) continue;
-    const uint32_t b = fd_div(w, a.tiles_per_block);
+    uint32_t b = fd_div(w, a.tiles_per_block);
     const uint32_t tile = w - b * a.tiles_per_block.d;
-    const int32_t sb = worklist[b];  // -1: the source id was out of range, block is skipped
-    regroup_tile<SL, DL, VEC, THREADS, UNROLL, NT>(a, layer, b, tile, sb, threadIdx.x);
+    if (merge) b = a.pass ? local_base + b : (b < local_base ? b : b + local_n);
+    int32_t sb = worklist[b];  // -1: the source id was out of range, block is skipped
+    const char* one_pool = nullptr;
+    if (merge) {
+      const uint32_t id = sb < 0 ? 0u : (uint32_t)sb;
+      const uint32_t old_block = fd_div(id, a.n_inst);
+      one_pool = a.src[id - old_block * a.n_inst.d];
+      if (sb >= 0) sb = (int32_t)old_block;
+    }
+    regroup_tile<SL, DL, VEC, THREADS, UNROLL, NT>(a, layer, b, tile, sb, threadIdx.x, one_pool);
   }
 }
 
@@ -514,7 +567,9 @@ struct KVLaunch {
   size_t lds = 0;
 };
 
-bool kv_launch_shape(const amoeba_plan_s* p, int vec, KVLaunch* out, std::string* err) {
+// multi: the merge of several instances (always the three-kernel direct gather).
+bool kv_launch_shape(const amoeba_plan_s* p, int vec, bool multi, KVLaunch* out,
+                     std::string* err) {
   const amoeba_model_shape& s = p->shape;
   const uint64_t head_vec_bytes = uint64_t(s.head_dim) * s.elem_bytes;
   const uint32_t B = uint32_t(s.kv_block_tokens);
@@ -565,7 +620,7 @@ bool kv_launch_shape(const amoeba_plan_s* p, int vec, KVLaunch* out, std::string
   const bool convert = s.kv_layout_src != s.kv_layout_dst;
   const bool want_staged =
       p->tune.kv_staged == 1 || (p->tune.kv_staged == 0 && head_vec_bytes <= 128);
-  if (convert && vec == 16 && want_staged && head_vec_bytes <= 4096) {
+  if (convert && vec == 16 && want_staged && head_vec_bytes <= 4096 && !multi) {
     // Tile: 1 KiB runs on the destination's side first (scattered writes cost more than
     // scattered reads), then as much of the other axis as the lanes' vectors allow.
     // Measured best: 256 lanes x 2 vectors (8 KiB); 4 vectors per lane lose 3-8 %.
@@ -610,7 +665,7 @@ bool kv_launch_shape(const amoeba_plan_s* p, int vec, KVLaunch* out, std::string
   }
 
   // A small table: scan, table and regroup in one launch of single-wavefront workgroups.
-  if (vec == 16 && p->tune.kv_small != 1 && p->tune.kv_unroll == 0 && p->tune.kv_threads == 0 &&
+  if (vec == 16 && !multi && p->tune.kv_small != 1 && p->tune.kv_unroll == 0 && p->tune.kv_threads == 0 &&
       p->tune.nontemporal != 2 && cells > 0 && cells <= kSmallCells &&
       uint32_t(s.num_seqs) <= kSmallSeqs && s.dst_pool_blocks > 0) {
     L.small = true;
@@ -636,12 +691,158 @@ bool kv_launch_geometry(const amoeba_plan_s* p, int align_bytes, LaunchShape* ou
   const uint64_t head_vec_bytes = uint64_t(p->shape.head_dim) * p->shape.elem_bytes;
   const int vec = common_alignment(head_vec_bytes | uint64_t(align_bytes));
   KVLaunch L;
-  if (!kv_launch_shape(p, vec, &L, err)) return false;
+  if (!kv_launch_shape(p, vec, false, &L, err)) return false;
   out->grid_x = L.grid.x;
   out->grid_y = L.grid.y;
   out->threads = uint32_t(L.threads);
   out->items = uint64_t(p->shape.dst_pool_blocks) * L.tiles_per_block;
   return true;
+}
+
+namespace {
+
+// Geometry fields of the regroup arguments that follow from the plan and the vector width.
+void fill_geometry(KVArgs* a, const amoeba_plan_s* p, int vec, const KVLaunch& L) {
+  const amoeba_model_shape& s = p->shape;
+  const uint32_t B = uint32_t(s.kv_block_tokens);
+  const uint32_t dv = uint32_t(uint64_t(s.head_dim) * s.elem_bytes / vec);
+  a->src_layer_stride = uint64_t(s.src_pool_blocks) * p->block_bytes_src;
+  a->dst_layer_stride = uint64_t(s.dst_pool_blocks) * p->block_bytes_dst;
+  a->src_block_bytes = uint64_t(p->block_bytes_src);
+  a->dst_block_bytes = uint64_t(p->block_bytes_dst);
+  a->heads_src = make_fastdiv(uint32_t(p->heads_src));
+  a->heads_dst = make_fastdiv(uint32_t(p->heads_dst));
+  a->dv = make_fastdiv(dv);
+  a->head_vecs = make_fastdiv(2u * B * dv);
+  a->block_vecs = uint32_t(uint64_t(p->block_bytes_dst) / vec);
+  a->tiles_per_block = make_fastdiv(uint32_t(L.tiles_per_block));
+  a->n_inst = make_fastdiv(1);
+  a->pass = 0;
+}
+
+// Scan of the (merged) sequence lengths, then the (merged) table and the work list.
+int launch_scan_and_table(const amoeba_plan_s* p, const SeqInputs& in, int32_t* dst_block_tables,
+                          int32_t* ws, hipStream_t stream, std::string* err) {
+  const amoeba_model_shape& s = p->shape;
+  hipLaunchKernelGGL(kv_scan_kernel, dim3(1), dim3(kScanThreads), 0, stream, in,
+                     uint32_t(s.max_blocks_per_seq), uint32_t(s.kv_block_tokens),
+                     int64_t(s.dst_pool_blocks), ws);
+  if (!hip_ok("kv scan kernel launch failed", err)) return AMOEBA_ERR_HIP;
+  const uint64_t cells = uint64_t(in.n_inst) * in.seqs.d * uint64_t(s.max_blocks_per_seq);
+  if (cells) {
+    const uint32_t grid = uint32_t((cells + kThreads - 1) / kThreads);
+    hipLaunchKernelGGL(kv_table_kernel, dim3(grid), dim3(kThreads), 0, stream, in,
+                       dst_block_tables, make_fastdiv(uint32_t(s.max_blocks_per_seq)),
+                       uint32_t(s.kv_block_tokens), int64_t(s.src_pool_blocks), ws);
+    if (!hip_ok("kv table kernel launch failed", err)) return AMOEBA_ERR_HIP;
+  }
+  return AMOEBA_OK;
+}
+
+void launch_direct(const amoeba_model_shape& s, const KVLaunch& L, dim3 grid, bool nt,
+                   hipStream_t stream, const KVArgs& a) {
+  const bool sh = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR, dh = s.kv_layout_dst == AMOEBA_KV_HEAD_MAJOR;
+  if (sh && dh)
+    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_HEAD_MAJOR>(L.vec, L.threads, L.unroll, nt, grid, stream, a);
+  else if (sh && !dh)
+    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(L.vec, L.threads, L.unroll, nt, grid, stream, a);
+  else if (!sh && dh)
+    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR>(L.vec, L.threads, L.unroll, nt, grid, stream, a);
+  else
+    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(L.vec, L.threads, L.unroll, nt, grid, stream, a);
+}
+
+}  // namespace
+
+int launch_merge_kv_base(const amoeba_plan_s* p, int32_t* ws, const void* const* pools,
+                         const int32_t* const* src_block_tables, const int32_t* const* seq_lens,
+                         void* new_pool, int32_t* dst_block_tables, hipStream_t stream,
+                         std::string* err) {
+  const amoeba_model_shape& s = p->shape;
+  if (p->kp % p->k || p->kp / p->k < 2 ||
+      uint64_t(s.src_pool_blocks) * uint64_t(p->kp / p->k) > uint64_t(INT32_MAX)) {
+    *err = "the plan is not a merge of instances (needs dst_tp = m * src_tp, m >= 2, "
+           "src_pool_blocks * m < 2^31)";
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  const uint32_t m = uint32_t(p->kp / p->k), g = uint32_t(p->rp) % m;
+  const uint64_t S = uint64_t(s.num_seqs), W = uint64_t(s.max_blocks_per_seq);
+  const uint64_t cells = uint64_t(m) * S * W;
+  if (cells >= (uint64_t(1) << 32) - kThreads) {
+    *err = "merged block table has 2^32 cells or more";
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  if (!pools || (S && !seq_lens) || (cells && (!src_block_tables || !dst_block_tables))) {
+    *err = "a pools, seq_lens or table argument is NULL";
+    return AMOEBA_ERR_INVALID_ARG;
+  }
+  const uint64_t src_layer = uint64_t(s.src_pool_blocks) * p->block_bytes_src,
+                 dst_layer = uint64_t(s.dst_pool_blocks) * p->block_bytes_dst;
+  const uint64_t src_bytes = src_layer * s.kv_layers, dst_bytes = dst_layer * s.kv_layers;
+  const uint64_t d0 = reinterpret_cast<uint64_t>(new_pool);
+  if (!d0 && dst_bytes) { *err = "new_pool is NULL"; return AMOEBA_ERR_INVALID_ARG; }
+  SeqInputs in;
+  KVArgs a;
+  uint64_t bits = uint64_t(s.head_dim) * s.elem_bytes | d0;
+  for (uint32_t i = 0; i < AMOEBA_MAX_TP; ++i) {
+    in.lens[i] = in.tables[i] = nullptr;
+    a.src[i] = nullptr;
+  }
+  for (uint32_t i = 0; i < m; ++i) {
+    if ((S && !seq_lens[i]) || (cells && !src_block_tables[i])) {
+      *err = "a seq_lens or block table pointer is NULL";
+      return AMOEBA_ERR_INVALID_ARG;
+    }
+    in.lens[i] = S ? seq_lens[i] : nullptr;
+    in.tables[i] = cells ? src_block_tables[i] : nullptr;
+    const uint64_t s0 = reinterpret_cast<uint64_t>(pools[i]);
+    if (!s0 && src_bytes) { *err = "a pool pointer is NULL"; return AMOEBA_ERR_INVALID_ARG; }
+    if (s0 < d0 + dst_bytes && d0 < s0 + src_bytes) {
+      *err = "new_pool overlaps a source pool (the base solution needs a second pool)";
+      return AMOEBA_ERR_INVALID_ARG;
+    }
+    bits |= s0;
+    a.src[i] = static_cast<const char*>(pools[i]);
+  }
+  in.seqs = make_fastdiv(uint32_t(std::max<uint64_t>(S, 1)));
+  in.n_inst = S ? m : 0;   // no sequences: nothing to scan
+  in.local_inst = g;
+  const int vec = common_alignment(bits);
+  KVLaunch L;
+  if (!kv_launch_shape(p, vec, true, &L, err)) return AMOEBA_ERR_INVALID_ARG;
+  const bool nt = p->tune.nontemporal != 2;
+
+  const int rc = launch_scan_and_table(p, in, dst_block_tables, ws, stream, err);
+  if (rc != AMOEBA_OK) return rc;
+  if (cells == 0 || s.dst_pool_blocks == 0) return AMOEBA_OK;
+
+  fill_geometry(&a, p, vec, L);
+  a.dst = static_cast<char*>(new_pool);
+  a.ws = ws;
+  a.num_seqs = uint32_t(m * S);
+  // rank r' = s*m + g keeps heads [g * heads_dst, (g + 1) * heads_dst) of an old block
+  a.head0 = g * uint32_t(p->heads_dst);
+  a.rank_lo = a.rank_hi = 0;
+  a.n_src = 1;
+  a.src_lo = a.src_hi = nullptr;  // the pool comes from the block's instance
+  a.n_inst = make_fastdiv(m);
+  // Pass 1, migration: the blocks of the other instances; the grid is the one for the whole
+  // (the local instance's share of it idles).  Pass 2, de-fragmentation: the local blocks,
+  // with the grid an even share of the bound (instances are balanced by the scheduler; if
+  // this one holds more, workgroups stride).
+  a.pass = 0;
+  launch_direct(s, L, L.grid, nt, stream, a);
+  if (!hip_ok("kv migration kernel launch failed", err)) return AMOEBA_ERR_HIP;
+  a.pass = 1;
+  dim3 local_grid = L.grid;
+  const int64_t bound = p->tune.kv_blocks_hint > 0 ? p->tune.kv_blocks_hint : s.kv_blocks_bound;
+  if (bound > 0) {
+    const uint64_t want = (uint64_t(bound) + m - 1) / m * L.tiles_per_block;
+    local_grid.x = clamp_grid_x(grid_for_items(want, uint64_t(L.grid.x)), uint32_t(L.threads));
+  }
+  launch_direct(s, L, local_grid, nt, stream, a);
+  if (!hip_ok("kv de-fragmentation kernel launch failed", err)) return AMOEBA_ERR_HIP;
+  return AMOEBA_OK;
 }
 
 int launch_reshard_kv(const amoeba_plan_s* p, int32_t* ws, const void* const* src_blocks,
@@ -680,17 +881,13 @@ int launch_reshard_kv(const amoeba_plan_s* p, int32_t* ws, const void* const* sr
   }
   const int vec = common_alignment(bits);
   KVLaunch L;
-  if (!kv_launch_shape(p, vec, &L, err)) return AMOEBA_ERR_INVALID_ARG;
+  if (!kv_launch_shape(p, vec, false, &L, err)) return AMOEBA_ERR_INVALID_ARG;
   const bool nt = p->tune.nontemporal != 2;
 
   const uint32_t B = uint32_t(s.kv_block_tokens);
-  const uint32_t dv = uint32_t(head_vec_bytes / vec);  // vectors of one head vector
+  fill_geometry(&a, p, vec, L);
   a.dst = static_cast<char*>(dst_blocks);
   a.ws = ws;
-  a.src_layer_stride = src_layer;
-  a.dst_layer_stride = dst_layer;
-  a.src_block_bytes = uint64_t(p->block_bytes_src);
-  a.dst_block_bytes = uint64_t(p->block_bytes_dst);
   a.num_seqs = uint32_t(s.num_seqs);
   a.head0 = uint32_t(p->rp * p->heads_dst);
   a.rank_lo = a.head0 / uint32_t(p->heads_src);
@@ -698,12 +895,6 @@ int launch_reshard_kv(const amoeba_plan_s* p, int32_t* ws, const void* const* sr
   a.n_src = a.rank_hi - a.rank_lo + 1;
   a.src_lo = a.src[a.rank_lo];
   a.src_hi = a.src[a.rank_hi];
-  a.heads_src = make_fastdiv(uint32_t(p->heads_src));
-  a.heads_dst = make_fastdiv(uint32_t(p->heads_dst));
-  a.dv = make_fastdiv(dv);
-  a.head_vecs = make_fastdiv(2u * B * dv);
-  a.block_vecs = uint32_t(uint64_t(p->block_bytes_dst) / vec);
-  a.tiles_per_block = make_fastdiv(uint32_t(L.tiles_per_block));
   const bool sh = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR, dh = s.kv_layout_dst == AMOEBA_KV_HEAD_MAJOR;
 
   if (L.small) {
@@ -720,20 +911,16 @@ int launch_reshard_kv(const amoeba_plan_s* p, int32_t* ws, const void* const* sr
     return AMOEBA_OK;
   }
 
-  // 1. scan
-  hipLaunchKernelGGL(kv_scan_kernel, dim3(1), dim3(kScanThreads), 0, stream, seq_lens,
-                     uint32_t(s.num_seqs), uint32_t(s.max_blocks_per_seq),
-                     uint32_t(s.kv_block_tokens), int64_t(s.dst_pool_blocks), ws);
-  if (!hip_ok("kv scan kernel launch failed", err)) return AMOEBA_ERR_HIP;
-  // 2. tables
-  if (cells) {
-    const uint32_t grid = uint32_t((cells + kThreads - 1) / kThreads);
-    hipLaunchKernelGGL(kv_table_kernel, dim3(grid), dim3(kThreads), 0, stream, seq_lens,
-                       src_block_tables, dst_block_tables, uint32_t(s.num_seqs),
-                       make_fastdiv(uint32_t(s.max_blocks_per_seq)), uint32_t(s.kv_block_tokens),
-                       int64_t(s.src_pool_blocks), ws);
-    if (!hip_ok("kv table kernel launch failed", err)) return AMOEBA_ERR_HIP;
-  }
+  // 1. scan, 2. tables
+  SeqInputs in;
+  for (int r = 0; r < AMOEBA_MAX_TP; ++r) in.lens[r] = in.tables[r] = nullptr;
+  in.lens[0] = seq_lens;
+  in.tables[0] = src_block_tables;
+  in.seqs = make_fastdiv(uint32_t(std::max<int32_t>(s.num_seqs, 1)));
+  in.n_inst = s.num_seqs > 0 ? 1 : 0;
+  in.local_inst = 0;
+  const int rc = launch_scan_and_table(p, in, dst_block_tables, ws, stream, err);
+  if (rc != AMOEBA_OK) return rc;
   // 3. regroup
   if (cells == 0 || s.dst_pool_blocks == 0) return AMOEBA_OK;
 
@@ -779,14 +966,7 @@ int launch_reshard_kv(const amoeba_plan_s* p, int32_t* ws, const void* const* sr
     return AMOEBA_OK;
   }
 
-  if (sh && dh)
-    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, L.threads, L.unroll, nt, L.grid, stream, a);
-  else if (sh && !dh)
-    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, L.threads, L.unroll, nt, L.grid, stream, a);
-  else if (!sh && dh)
-    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR>(vec, L.threads, L.unroll, nt, L.grid, stream, a);
-  else
-    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(vec, L.threads, L.unroll, nt, L.grid, stream, a);
+  launch_direct(s, L, L.grid, nt, stream, a);
   if (!hip_ok("kv regroup kernel launch failed", err)) return AMOEBA_ERR_HIP;
   return AMOEBA_OK;
 }
