@@ -51,11 +51,12 @@ def parse():
                          "on the same sequence table, e.g. 64-byte head vectors)")
     ap.add_argument("--kv-heads", type=int, default=0, help="override n_kv_heads = n_q_heads")
     ap.add_argument("--tune", default="", help="knob=value,... (AMOEBA_TUNE_* names, lower case)")
-    ap.add_argument("--mode", default="reshard", choices=["reshard", "merge-inplace", "merge-naive", "weights-padded", "overlap"],
+    ap.add_argument("--mode", default="reshard", choices=["reshard", "merge-inplace", "merge-naive", "merge-base", "weights-padded", "overlap"],
                     help="reshard: the TP k -> k' hot path (default, the headline metric); "
                          "merge-inplace: m x TP1 instances -> TP m, KV cache only, in place; "
-                         "merge-naive: the same scenario the paper's base way (token-first "
-                         "blocks, every block of every instance moved into a fresh pool); "
+                         "merge-base (alias merge-naive): the same scenario the paper's base "
+                         "way (token-first blocks, migration pass + de-fragmentation pass into "
+                         "a second pool); "
                          "weights-padded: TP1 <-> TP4 weight transformation with the padded "
                          "FFN layout against the dense layout (the paper's partial swap); "
                          "overlap: n layers per step resharded on a side stream while a synthetic "
@@ -84,7 +85,7 @@ def main():
     torch.cuda.set_device(0)
     if args.mode == "merge-inplace":
         return merge_inplace(args)
-    if args.mode == "merge-naive":
+    if args.mode in ("merge-naive", "merge-base"):
         return merge_naive(args)
     if args.mode == "weights-padded":
         return weights_padded(args)
@@ -610,11 +611,14 @@ def _instances(w, m):
 
 
 def merge_naive(args):
-    """The paper's base solution for the same 4 x TP1 -> TP4 scenario, restated on one GPU:
-    token-first blocks, so the heads a worker keeps are strided pieces inside every block and
-    must be compacted (de-fragmented) just like the heads it receives.  Every block of every
-    instance is therefore regrouped into a fresh pool: m amoeba_reshard_kv calls (TP1 -> TPm,
-    token-first on both sides), one per source instance.  One step = those m calls."""
+    """The paper's base solution for the same m x TP1 -> TP m scenario (Sec. 3.1: migration and
+    de-fragmentation on token-first blocks): the heads a worker keeps are strided pieces inside
+    every block and must be compacted just like the heads it receives, so every block of every
+    instance is regrouped into a second pool.  One step = one amoeba_merge_kv_base call (scan,
+    table, migration pass over the remote instances' blocks, de-fragmentation pass over the
+    local ones); the passes are also timed separately through the kernel events of one extra
+    call each way (migration only = the call on a copy of the inputs whose local instance has
+    no sequences, and the other way round)."""
     import numpy as np
     import torch
 
@@ -625,63 +629,72 @@ def merge_naive(args):
     m, rank = args.instances, 1 % args.instances
     per, nb, tables, S, P, W = _instances(w, m)
     L = args.kv_layers or w.n_layers
-    plans, dsts, outs, srcs = [], [], [], []
+    lay = {"hm": ab.KV_HEAD_MAJOR, "tm": ab.KV_TOKEN_MAJOR}
+    layout = "tm-tm" if args.layout == "hm-hm" else args.layout   # the base solution is token-first
+    lay_s, lay_d = (lay[x] for x in layout.split("-"))
+    total_blocks = sum(int(x.sum()) for x in nb)
+    local_blocks = int(nb[rank].sum())
+    shape = ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn_dim,
+                          elem_bytes=2, kv_block_tokens=w.block_tokens, kv_layout_src=lay_s,
+                          kv_layout_dst=lay_d, kv_layers=L, num_seqs=S, max_blocks_per_seq=W,
+                          src_pool_blocks=P, dst_pool_blocks=total_blocks,
+                          kv_blocks_bound=0 if args.no_bound else total_blocks)
+    plan = ab.amoeba_plan(shape, 1, m, rank)
+    bs, bd = ab.amoeba_plan_kv_block_bytes(plan, 0), ab.amoeba_plan_kv_block_bytes(plan, 1)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(0xA30EBA10 + w.index)
+    pools = []
     for g in range(m):
-        need = int(nb[g].sum())
-        shape = ab.ModelShape(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim,
-                              w.ffn_dim, elem_bytes=2, kv_block_tokens=w.block_tokens,
-                              kv_layout_src=ab.KV_TOKEN_MAJOR, kv_layout_dst=ab.KV_TOKEN_MAJOR,
-                              kv_layers=L, num_seqs=S, max_blocks_per_seq=W, src_pool_blocks=P,
-                              dst_pool_blocks=need, kv_blocks_bound=need)
-        plan = ab.amoeba_plan(shape, 1, m, rank)
-        plans.append(plan)
-        bs, bd = ab.amoeba_plan_kv_block_bytes(plan, 0), ab.amoeba_plan_kv_block_bytes(plan, 1)
         t = torch.empty(L * P * bs // 2, dtype=torch.bfloat16, device="cuda")
         for a in range(0, t.numel(), 1 << 28):
             t[a:a + (1 << 28)].normal_(0.0, 0.02, generator=gen)
-        srcs.append(t)
-        dsts.append(torch.empty(L * need * bd // 2, dtype=torch.bfloat16, device="cuda"))
-        outs.append(torch.empty((S, W), dtype=torch.int32, device="cuda"))
+        pools.append(t)
+    new_pool = torch.empty(L * total_blocks * bd // 2, dtype=torch.bfloat16, device="cuda")
+    out_table = torch.empty((m * S, W), dtype=torch.int32, device="cuda")
     tabs_d = [torch.from_numpy(t).cuda() for t in tables]
     lens_d = [torch.from_numpy(x.astype(np.int32)).cuda() for x in per]
+    zero = torch.zeros(S, dtype=torch.int32, device="cuda")
 
-    def step():
-        for g in range(m):
-            ab.amoeba_reshard_kv(plans[g], [srcs[g]], tabs_d[g], lens_d[g], dsts[g], outs[g])
+    def step(lens=lens_d):
+        ab.amoeba_merge_kv_base(plan, pools, tabs_d, lens, new_pool, out_table)
 
-    for _ in range(args.warmup):
-        step()
-    for g in range(m):
-        rc, n = ab.amoeba_kv_status(plans[g])
-        assert rc == ab.OK and n == int(nb[g].sum())
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    dev_ms = e0.elapsed_time(e1) / args.steps
-    total_blocks = sum(int(x.sum()) for x in nb)
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps, e0.elapsed_time(e1) / args.steps
+
+    ms, dev_ms = timed(step)
+    rc, n = ab.amoeba_kv_status(plan)
+    assert rc == ab.OK and n == total_blocks, (rc, n, ab.amoeba_last_error())
+    only_remote = [zero if g == rank else lens_d[g] for g in range(m)]
+    only_local = [lens_d[g] if g == rank else zero for g in range(m)]
+    _, migrate_ms = timed(lambda: step(only_remote))
+    _, defrag_ms = timed(lambda: step(only_local))
     alg = 2 * total_blocks * bd * L
     out = {
-        "metric": "naive KV merge (token-first, migrate + de-fragment into a fresh pool), "
+        "metric": "base KV merge of Sec. 3.1 (migration + de-fragmentation into a second pool), "
                   "m x TP1 -> TP m, one target rank",
         "value": round(alg / (ms * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16",
         "data": "synthetic",
         "config": {"workload": f"{w.name} KV cache: {m} x TP1 -> TP{m} rank {rank}, {L} layers, "
-                               f"{m} x {S} seqs, {total_blocks} blocks of {w.block_tokens}",
+                               f"{m} x {S} seqs, {total_blocks} blocks of {w.block_tokens} "
+                               f"({local_blocks} local), layout {layout}",
                    "alg_bytes": alg, "extra_device_memory_bytes": total_blocks * bd * L,
-                   "device_ms": round(dev_ms, 4)},
+                   "device_ms": round(dev_ms, 4),
+                   "migration_pass_only_ms": round(migrate_ms, 4),
+                   "defragmentation_pass_only_ms": round(defrag_ms, 4)},
     }
-    for pl in plans:
-        pl.close()
+    plan.close()
     print(json.dumps(out), flush=True)
 
 

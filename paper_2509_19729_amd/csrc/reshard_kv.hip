@@ -284,20 +284,21 @@ __device__ __forceinline__ void regroup_tile(const KVArgs& a, uint32_t layer, ui
 // blockIdx.y = layer; blockIdx.x strides over (new block, tile) of that layer.
 // `ws` is only read here (the scan and table kernels that fill it have finished),
 // which lets the uniform lookups go through scalar loads.
-template <int SL, int DL, int VEC, int THREADS, int UNROLL, bool NT>
+// MERGE: the two passes of the base solution of Sec. 3.1 over m instances' pools (a
+// template parameter, not a run-time branch: even uniform scalar work in this kernel's
+// short prologue costs 1-2 % of the rate).
+template <int SL, int DL, int VEC, int THREADS, int UNROLL, bool NT, bool MERGE>
 __global__ void __launch_bounds__(THREADS)
 kv_regroup_kernel(const KVArgs a, const int32_t* __restrict__ ws) {
   const uint32_t layer = blockIdx.y;
   const uint32_t total = (uint32_t)ws[kWsTotal];
   const int32_t* __restrict__ worklist = ws + kWsHeader + a.num_seqs;
-  // A merge runs this kernel twice: the migration pass takes the blocks outside the local
-  // instance's id range [local_base, local_base + local_n), the de-fragmentation pass the
-  // ones inside.  (All of this is uniform: scalar loads and scalar arithmetic.)
-  const bool merge = a.n_inst.d > 1;
-  const uint32_t local_base = merge ? (uint32_t)ws[kWsLocalBase] : 0u;
-  const uint32_t local_n = merge ? (uint32_t)ws[kWsLocalCount] : 0u;
-  const uint32_t n_blocks = !merge ? total : (a.pass ? local_n : total - local_n);
-  const uint32_t n_items = n_blocks * a.tiles_per_block.d;  // < 2^32, bounded on the host
+  // the migration pass takes the blocks outside the local instance's id range
+  // [local_base, local_base + local_n), the de-fragmentation pass the ones inside
+  const uint32_t local_base = MERGE ? (uint32_t)ws[kWsLocalBase] : 0u;
+  const uint32_t local_n = MERGE ? (uint32_t)ws[kWsLocalCount] : 0u;
+  const uint32_t n_blocks = !MERGE ? total : (a.pass ? local_n : total - local_n);
+  const uint32_t n_items = n_blocks * a.tiles_per_block.d;  // < 2^31, bounded on the host
   // Items are taken in the XCD-chunked order (see xcd_item()): +4 % for workgroups of four
   // wavefronts, +1-2 % for single-wavefront ones on the block gather (a plain copy with
   // single-wavefront workgroups does not gain from it).
@@ -308,10 +309,10 @@ kv_regroup_kernel(const KVArgs a, const int32_t* __restrict__ ws) {
     if (w >= n_items) continue;
     uint32_t b = fd_div(w, a.tiles_per_block);
     const uint32_t tile = w - b * a.tiles_per_block.d;
-    if (merge) b = a.pass ? local_base + b : (b < local_base ? b : b + local_n);
+    if (MERGE) b = a.pass ? local_base + b : (b < local_base ? b : b + local_n);
     int32_t sb = worklist[b];  // -1: the source id was out of range, block is skipped
     const char* one_pool = nullptr;
-    if (merge) {
+    if (MERGE) {  // a work-list entry is source id * m + instance
       const uint32_t id = sb < 0 ? 0u : (uint32_t)sb;
       const uint32_t old_block = fd_div(id, a.n_inst);
       one_pool = a.src[id - old_block * a.n_inst.d];
@@ -512,39 +513,55 @@ kv_regroup_staged_kernel(const KVArgs a, const KVStagedGeom g, const int32_t* __
 
 namespace {
 
-template <int SL, int DL, int VEC, int THREADS, int UNROLL>
+template <int SL, int DL, int VEC, int THREADS, int UNROLL, bool MERGE>
 void launch_nt(bool nt, dim3 grid, hipStream_t stream, const KVArgs& a) {
   if (nt)
-    hipLaunchKernelGGL((kv_regroup_kernel<SL, DL, VEC, THREADS, UNROLL, true>), grid,
+    hipLaunchKernelGGL((kv_regroup_kernel<SL, DL, VEC, THREADS, UNROLL, true, MERGE>), grid,
                        dim3(THREADS), 0, stream, a, a.ws);
   else
-    hipLaunchKernelGGL((kv_regroup_kernel<SL, DL, VEC, THREADS, UNROLL, false>), grid,
+    hipLaunchKernelGGL((kv_regroup_kernel<SL, DL, VEC, THREADS, UNROLL, false, MERGE>), grid,
                        dim3(THREADS), 0, stream, a, a.ws);
 }
 
 template <int SL, int DL, int THREADS>
 void launch_unroll(int unroll, bool nt, dim3 grid, hipStream_t stream, const KVArgs& a) {
   switch (unroll) {
-    case 2: launch_nt<SL, DL, 16, THREADS, 2>(nt, grid, stream, a); break;
-    case 4: launch_nt<SL, DL, 16, THREADS, 4>(nt, grid, stream, a); break;
-    default: launch_nt<SL, DL, 16, THREADS, 1>(nt, grid, stream, a); break;
+    case 2: launch_nt<SL, DL, 16, THREADS, 2, false>(nt, grid, stream, a); break;
+    case 4: launch_nt<SL, DL, 16, THREADS, 4, false>(nt, grid, stream, a); break;
+    default: launch_nt<SL, DL, 16, THREADS, 1, false>(nt, grid, stream, a); break;
   }
 }
 
+// merge: one vector per lane only (the launch shape that measured best)
 template <int SL, int DL>
-void launch_vec(int vec, int threads, int unroll, bool nt, dim3 grid, hipStream_t stream,
-                const KVArgs& a) {
+void launch_vec(int vec, int threads, int unroll, bool nt, bool merge, dim3 grid,
+                hipStream_t stream, const KVArgs& a) {
+  if (merge) {
+    if (vec == 16) {
+      if (threads == 64) launch_nt<SL, DL, 16, 64, 1, true>(nt, grid, stream, a);
+      else launch_nt<SL, DL, 16, 256, 1, true>(nt, grid, stream, a);
+    } else if (vec == 8) {
+      launch_nt<SL, DL, 8, 256, 1, true>(true, grid, stream, a);
+    } else if (vec == 4) {
+      launch_nt<SL, DL, 4, 256, 1, true>(true, grid, stream, a);
+    } else if (vec == 2) {
+      launch_nt<SL, DL, 2, 256, 1, true>(true, grid, stream, a);
+    } else {
+      launch_nt<SL, DL, 1, 256, 1, true>(true, grid, stream, a);
+    }
+    return;
+  }
   if (vec == 16) {
     if (threads == 64) launch_unroll<SL, DL, 64>(unroll, nt, grid, stream, a);
     else launch_unroll<SL, DL, 256>(unroll, nt, grid, stream, a);
   } else if (vec == 8) {
-    launch_nt<SL, DL, 8, 256, 1>(true, grid, stream, a);
+    launch_nt<SL, DL, 8, 256, 1, false>(true, grid, stream, a);
   } else if (vec == 4) {
-    launch_nt<SL, DL, 4, 256, 1>(true, grid, stream, a);
+    launch_nt<SL, DL, 4, 256, 1, false>(true, grid, stream, a);
   } else if (vec == 2) {
-    launch_nt<SL, DL, 2, 256, 1>(true, grid, stream, a);
+    launch_nt<SL, DL, 2, 256, 1, false>(true, grid, stream, a);
   } else {
-    launch_nt<SL, DL, 1, 256, 1>(true, grid, stream, a);
+    launch_nt<SL, DL, 1, 256, 1, false>(true, grid, stream, a);
   }
 }
 
@@ -562,6 +579,7 @@ struct KVLaunch {
   bool small = false;    // scan, table and regroup in one launch (kv_small_kernel)
   int vec = 16, threads = 64, unroll = 1;  // unroll: vectors per lane (staged: per side)
   uint64_t tiles_per_block = 0;
+  uint64_t basis = 0;    // items per layer the grid was sized for (capacity, or the bound)
   dim3 grid;
   KVStagedGeom g;
   size_t lds = 0;
@@ -581,7 +599,7 @@ bool kv_launch_shape(const amoeba_plan_s* p, int vec, bool multi, KVLaunch* out,
   KVLaunch L;
   L.vec = vec;
   int unroll = p->tune.kv_unroll, threads = p->tune.kv_threads;
-  if (vec != 16 || (unroll != 2 && unroll != 4)) unroll = 1;
+  if (vec != 16 || multi || (unroll != 2 && unroll != 4)) unroll = 1;
   if (vec != 16) threads = 256;
   else if (threads != 256 && threads != 64)
     // One wavefront per 1 KiB tile is fastest when the grid is tight (6.45 TB/s against 6.4
@@ -605,10 +623,12 @@ bool kv_launch_shape(const amoeba_plan_s* p, int vec, bool multi, KVLaunch* out,
     uint64_t grid =
         std::max<uint64_t>(uint64_t(1) << 16, (uint64_t(1) << 27) / uint64_t(s.kv_layers));
     if (p->tune.kv_grid > 0) grid = uint64_t(p->tune.kv_grid);
+    uint64_t basis = max_items;
     if (bound > 0)
-      grid = std::min<uint64_t>(grid, std::max<uint64_t>(1, uint64_t(bound) * tiles_per_block));
-    grid = grid_for_items(grid, max_items);
+      basis = std::min<uint64_t>(basis, std::max<uint64_t>(1, uint64_t(bound) * tiles_per_block));
+    grid = grid_for_items(std::min(grid, basis), max_items);
     *g = dim3(clamp_grid_x(grid, lanes), uint32_t(s.kv_layers));
+    L.basis = basis;
     return true;
   };
 
@@ -739,17 +759,17 @@ int launch_scan_and_table(const amoeba_plan_s* p, const SeqInputs& in, int32_t* 
   return AMOEBA_OK;
 }
 
-void launch_direct(const amoeba_model_shape& s, const KVLaunch& L, dim3 grid, bool nt,
+void launch_direct(const amoeba_model_shape& s, const KVLaunch& L, dim3 grid, bool nt, bool merge,
                    hipStream_t stream, const KVArgs& a) {
   const bool sh = s.kv_layout_src == AMOEBA_KV_HEAD_MAJOR, dh = s.kv_layout_dst == AMOEBA_KV_HEAD_MAJOR;
   if (sh && dh)
-    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_HEAD_MAJOR>(L.vec, L.threads, L.unroll, nt, grid, stream, a);
+    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_HEAD_MAJOR>(L.vec, L.threads, L.unroll, nt, merge, grid, stream, a);
   else if (sh && !dh)
-    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(L.vec, L.threads, L.unroll, nt, grid, stream, a);
+    launch_vec<AMOEBA_KV_HEAD_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(L.vec, L.threads, L.unroll, nt, merge, grid, stream, a);
   else if (!sh && dh)
-    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR>(L.vec, L.threads, L.unroll, nt, grid, stream, a);
+    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_HEAD_MAJOR>(L.vec, L.threads, L.unroll, nt, merge, grid, stream, a);
   else
-    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(L.vec, L.threads, L.unroll, nt, grid, stream, a);
+    launch_vec<AMOEBA_KV_TOKEN_MAJOR, AMOEBA_KV_TOKEN_MAJOR>(L.vec, L.threads, L.unroll, nt, merge, grid, stream, a);
 }
 
 }  // namespace
@@ -831,16 +851,17 @@ int launch_merge_kv_base(const amoeba_plan_s* p, int32_t* ws, const void* const*
   // with the grid an even share of the bound (instances are balanced by the scheduler; if
   // this one holds more, workgroups stride).
   a.pass = 0;
-  launch_direct(s, L, L.grid, nt, stream, a);
+  launch_direct(s, L, L.grid, nt, true, stream, a);
   if (!hip_ok("kv migration kernel launch failed", err)) return AMOEBA_ERR_HIP;
   a.pass = 1;
   dim3 local_grid = L.grid;
+  uint64_t local_basis = L.basis;
   const int64_t bound = p->tune.kv_blocks_hint > 0 ? p->tune.kv_blocks_hint : s.kv_blocks_bound;
   if (bound > 0) {
-    const uint64_t want = (uint64_t(bound) + m - 1) / m * L.tiles_per_block;
-    local_grid.x = clamp_grid_x(grid_for_items(want, uint64_t(L.grid.x)), uint32_t(L.threads));
+    local_basis = std::min<uint64_t>(L.basis, (uint64_t(bound) + m - 1) / m * L.tiles_per_block);
+    local_grid.x = clamp_grid_x(grid_for_items(local_basis, uint64_t(L.grid.x)), uint32_t(L.threads));
   }
-  launch_direct(s, L, local_grid, nt, stream, a);
+  launch_direct(s, L, local_grid, nt, true, stream, a);
   if (!hip_ok("kv de-fragmentation kernel launch failed", err)) return AMOEBA_ERR_HIP;
   return AMOEBA_OK;
 }
@@ -966,7 +987,7 @@ int launch_reshard_kv(const amoeba_plan_s* p, int32_t* ws, const void* const* sr
     return AMOEBA_OK;
   }
 
-  launch_direct(s, L, L.grid, nt, stream, a);
+  launch_direct(s, L, L.grid, nt, false, stream, a);
   if (!hip_ok("kv regroup kernel launch failed", err)) return AMOEBA_ERR_HIP;
   return AMOEBA_OK;
 }
