@@ -616,9 +616,7 @@ def merge_naive(args):
     every block and must be compacted just like the heads it receives, so every block of every
     instance is regrouped into a second pool.  One step = one amoeba_merge_kv_base call (scan,
     table, migration pass over the remote instances' blocks, de-fragmentation pass over the
-    local ones); the passes are also timed separately through the kernel events of one extra
-    call each way (migration only = the call on a copy of the inputs whose local instance has
-    no sequences, and the other way round)."""
+    local ones; the two passes are the two launches of the block gather in a kernel trace)."""
     import numpy as np
     import torch
 
@@ -653,31 +651,24 @@ def merge_naive(args):
     out_table = torch.empty((m * S, W), dtype=torch.int32, device="cuda")
     tabs_d = [torch.from_numpy(t).cuda() for t in tables]
     lens_d = [torch.from_numpy(x.astype(np.int32)).cuda() for x in per]
-    zero = torch.zeros(S, dtype=torch.int32, device="cuda")
+    def step():
+        ab.amoeba_merge_kv_base(plan, pools, tabs_d, lens_d, new_pool, out_table,
+                                0 if args.no_bound else local_blocks)
 
-    def step(lens=lens_d):
-        ab.amoeba_merge_kv_base(plan, pools, tabs_d, lens, new_pool, out_table)
-
-    def timed(fn):
-        for _ in range(args.warmup):
-            fn()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        e0.record()
-        for _ in range(args.steps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / args.steps, e0.elapsed_time(e1) / args.steps
-
-    ms, dev_ms = timed(step)
+    for _ in range(args.warmup):
+        step()
     rc, n = ab.amoeba_kv_status(plan)
     assert rc == ab.OK and n == total_blocks, (rc, n, ab.amoeba_last_error())
-    only_remote = [zero if g == rank else lens_d[g] for g in range(m)]
-    only_local = [lens_d[g] if g == rank else zero for g in range(m)]
-    _, migrate_ms = timed(lambda: step(only_remote))
-    _, defrag_ms = timed(lambda: step(only_local))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    dev_ms = e0.elapsed_time(e1) / args.steps
     alg = 2 * total_blocks * bd * L
     out = {
         "metric": "base KV merge of Sec. 3.1 (migration + de-fragmentation into a second pool), "
@@ -691,8 +682,8 @@ def merge_naive(args):
                                f"({local_blocks} local), layout {layout}",
                    "alg_bytes": alg, "extra_device_memory_bytes": total_blocks * bd * L,
                    "device_ms": round(dev_ms, 4),
-                   "migration_pass_only_ms": round(migrate_ms, 4),
-                   "defragmentation_pass_only_ms": round(defrag_ms, 4)},
+                   "migration_alg_bytes": 2 * (total_blocks - local_blocks) * bd * L,
+                   "defragmentation_alg_bytes": 2 * local_blocks * bd * L},
     }
     plan.close()
     print(json.dumps(out), flush=True)

@@ -296,13 +296,18 @@ int amoeba_merge_kv_inplace(const amoeba_plan_t* plan, void* local_pool,
  * Any layout pair works (the paper's base solution is token-first on both sides).  Enqueues
  * four kernels (scan, table, one block gather per pass), no host synchronisation, no memory
  * beyond the plan's workspace (4 * (8 + m*num_seqs + dst_pool_blocks) bytes) and new_pool
- * itself.  kv_blocks_bound bounds the blocks of all instances together.  Device-found
- * conditions are read with amoeba_kv_status() (total_blocks = blocks of all instances) and
- * are those of amoeba_reshard_kv().  Calls on one plan must not overlap in time.
+ * itself.  Grid sizing: the shape's kv_blocks_bound bounds the blocks of all instances
+ * together and local_blocks_bound (0 = unknown) those of the local instance g; with both
+ * given, the migration pass is sized for their difference and the de-fragmentation pass
+ * for the local bound (exact counts make both grids tight; any values are correct, since
+ * workgroups stride over what a grid does not cover).  Device-found conditions are read
+ * with amoeba_kv_status() (total_blocks = blocks of all instances) and are those of
+ * amoeba_reshard_kv().  Calls on one plan must not overlap in time.
  */
 int amoeba_merge_kv_base(const amoeba_plan_t* plan, const void* const* pools,
                          const int32_t* const* src_block_tables, const int32_t* const* seq_lens,
-                         void* new_pool, int32_t* dst_block_tables, void* stream);
+                         void* new_pool, int32_t* dst_block_tables, int64_t local_blocks_bound,
+                         void* stream);
 
 /* Like amoeba_kv_status() for the last amoeba_merge_kv_inplace() on this plan;
  * remote_blocks (may be NULL) receives the blocks copied per layer. */

@@ -142,7 +142,7 @@ def lib() -> ctypes.CDLL:
                                           ctypes.POINTER(vp), vp, vp]
     L.amoeba_merge_kv_base.restype = i32
     L.amoeba_merge_kv_base.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp),
-                                       ctypes.POINTER(vp), vp, vp, vp]
+                                       ctypes.POINTER(vp), vp, vp, i64, vp]
     L.amoeba_merge_kv_status.restype = i32
     L.amoeba_merge_kv_status.argtypes = [vp, vp, ctypes.POINTER(i64)]
     L.amoeba_plan_merge_factor.restype = i32
@@ -356,11 +356,13 @@ def amoeba_merge_kv_inplace(plan: Plan, local_pool, remote_pools, src_block_tabl
 
 
 def amoeba_merge_kv_base(plan: Plan, pools, src_block_tables, seq_lens, new_pool,
-                         dst_block_tables, stream=None, check: bool = True) -> int:
+                         dst_block_tables, local_blocks_bound: int = 0, stream=None,
+                         check: bool = True) -> int:
     m = max(plan.dst_tp // max(plan.src_tp, 1), 1)
     rc = lib().amoeba_merge_kv_base(plan.handle, _ptr_array(pools, m),
                                     _ptr_array(src_block_tables, m), _ptr_array(seq_lens, m),
-                                    _ptr(new_pool), _ptr(dst_block_tables), _stream_handle(stream))
+                                    _ptr(new_pool), _ptr(dst_block_tables), local_blocks_bound,
+                                    _stream_handle(stream))
     if check and rc != OK:
         raise AmoebaError(rc, amoeba_last_error())
     return rc

@@ -236,9 +236,10 @@ int amoeba_merge_kv_inplace(const amoeba_plan_t* plan, void* local_pool,
 
 int amoeba_merge_kv_base(const amoeba_plan_t* plan, const void* const* pools,
                          const int32_t* const* src_block_tables, const int32_t* const* seq_lens,
-                         void* new_pool, int32_t* dst_block_tables, void* stream) {
-  if (!plan) {
-    set_error("amoeba_merge_kv_base: NULL plan");
+                         void* new_pool, int32_t* dst_block_tables, int64_t local_blocks_bound,
+                         void* stream) {
+  if (!plan || local_blocks_bound < 0) {
+    set_error("amoeba_merge_kv_base: NULL plan or negative local_blocks_bound");
     return AMOEBA_ERR_INVALID_ARG;
   }
   if (!plan->workspace) {
@@ -254,6 +255,7 @@ int amoeba_merge_kv_base(const amoeba_plan_t* plan, const void* const* pools,
   std::string err;
   const int rc = amoeba::launch_merge_kv_base(plan, plan->workspace, pools, src_block_tables,
                                               seq_lens, new_pool, dst_block_tables,
+                                              local_blocks_bound,
                                               static_cast<hipStream_t>(stream), &err);
   if (rc != AMOEBA_OK) set_error("amoeba_merge_kv_base: " + err);
   else plan->status_ws = plan->workspace;

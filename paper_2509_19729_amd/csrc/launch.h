@@ -34,8 +34,8 @@ size_t static_kv_workspace_ints();
 // instances; ws: 8 + m * num_seqs + dst_pool_blocks int32 words.
 int launch_merge_kv_base(const amoeba_plan_s* p, int32_t* ws, const void* const* pools,
                          const int32_t* const* src_block_tables, const int32_t* const* seq_lens,
-                         void* new_pool, int32_t* dst_block_tables, hipStream_t stream,
-                         std::string* err);
+                         void* new_pool, int32_t* dst_block_tables, int64_t local_blocks_bound,
+                         hipStream_t stream, std::string* err);
 
 // Launch geometry of the three copy kernels for pointers aligned to align_bytes (host only).
 bool weights_launch_geometry(const amoeba_plan_s* p, int align_bytes, LaunchShape* out,

@@ -776,8 +776,8 @@ void launch_direct(const amoeba_model_shape& s, const KVLaunch& L, dim3 grid, bo
 
 int launch_merge_kv_base(const amoeba_plan_s* p, int32_t* ws, const void* const* pools,
                          const int32_t* const* src_block_tables, const int32_t* const* seq_lens,
-                         void* new_pool, int32_t* dst_block_tables, hipStream_t stream,
-                         std::string* err) {
+                         void* new_pool, int32_t* dst_block_tables, int64_t local_blocks_bound,
+                         hipStream_t stream, std::string* err) {
   const amoeba_model_shape& s = p->shape;
   if (p->kp % p->k || p->kp / p->k < 2 ||
       uint64_t(s.src_pool_blocks) * uint64_t(p->kp / p->k) > uint64_t(INT32_MAX)) {
@@ -846,22 +846,30 @@ int launch_merge_kv_base(const amoeba_plan_s* p, int32_t* ws, const void* const*
   a.n_src = 1;
   a.src_lo = a.src_hi = nullptr;  // the pool comes from the block's instance
   a.n_inst = make_fastdiv(m);
-  // Pass 1, migration: the blocks of the other instances; the grid is the one for the whole
-  // (the local instance's share of it idles).  Pass 2, de-fragmentation: the local blocks,
-  // with the grid an even share of the bound (instances are balanced by the scheduler; if
-  // this one holds more, workgroups stride).
+  // Pass 1, migration: the blocks of the other instances.  Pass 2, de-fragmentation: the
+  // local blocks.  Idle workgroups cost dispatch time (a pass sized for all blocks that only
+  // finds the local quarter takes almost as long as the whole), so each pass gets a grid of
+  // its own: the bound on all blocks minus the bound on the local ones, and the local bound.
+  // Without a local bound the passes share the whole bound evenly by instance count.  Past
+  // its grid a pass strides, so any bounds are correct.
+  const int64_t bound = p->tune.kv_blocks_hint > 0 ? p->tune.kv_blocks_hint : s.kv_blocks_bound;
+  auto pass_grid = [&](uint64_t blocks) {
+    dim3 g = L.grid;
+    if (bound > 0) {
+      const uint64_t want = std::max<uint64_t>(1, blocks) * L.tiles_per_block;
+      g.x = clamp_grid_x(grid_for_items(std::min<uint64_t>(want, L.grid.x), uint64_t(L.grid.x)),
+                         uint32_t(L.threads));
+    }
+    return g;
+  };
+  const uint64_t local_share = local_blocks_bound > 0 ? uint64_t(local_blocks_bound)
+                                                      : (uint64_t(std::max<int64_t>(bound, 0)) + m - 1) / m;
+  const uint64_t remote_share = uint64_t(bound) > local_share ? uint64_t(bound) - local_share : 1;
   a.pass = 0;
-  launch_direct(s, L, L.grid, nt, true, stream, a);
+  launch_direct(s, L, pass_grid(remote_share), nt, true, stream, a);
   if (!hip_ok("kv migration kernel launch failed", err)) return AMOEBA_ERR_HIP;
   a.pass = 1;
-  dim3 local_grid = L.grid;
-  uint64_t local_basis = L.basis;
-  const int64_t bound = p->tune.kv_blocks_hint > 0 ? p->tune.kv_blocks_hint : s.kv_blocks_bound;
-  if (bound > 0) {
-    local_basis = std::min<uint64_t>(L.basis, (uint64_t(bound) + m - 1) / m * L.tiles_per_block);
-    local_grid.x = clamp_grid_x(grid_for_items(local_basis, uint64_t(L.grid.x)), uint32_t(L.threads));
-  }
-  launch_direct(s, L, local_grid, nt, true, stream, a);
+  launch_direct(s, L, pass_grid(local_share), nt, true, stream, a);
   if (!hip_ok("kv de-fragmentation kernel launch failed", err)) return AMOEBA_ERR_HIP;
   return AMOEBA_OK;
 }

@@ -27,7 +27,7 @@ def _announce(request):
 
 
 def check_base(cfg, insts, m, k, rp, lay=(TM, TM), slack=3, expect=oracle.OK, tune=None, bound=0,
-               pool_blocks=None):
+               pool_blocks=None, local_bound=0):
     s = rp // m
     tabs, lens = [i["table"] for i in insts], [i["lens"] for i in insts]
     pools = [insts[g2]["pools"][s] for g2 in range(m)]
@@ -55,7 +55,7 @@ def check_base(cfg, insts, m, k, rp, lay=(TM, TM), slack=3, expect=oracle.OK, tu
     ab.amoeba_merge_kv_base(plan, [to_dev(a) for a in pools],
                             [torch.from_numpy(t).cuda() for t in tabs],
                             [torch.from_numpy(x).cuda() for x in lens],
-                            buf[guard:guard + n_bytes], out_table)
+                            buf[guard:guard + n_bytes], out_table, local_bound)
     st, n = ab.amoeba_kv_status(plan)
     code = {oracle.OK: ab.OK, oracle.ERR_OVERFLOW: ab.ERR_OVERFLOW,
             oracle.ERR_BLOCK_ID: ab.ERR_BLOCK_ID}[ost]
@@ -95,6 +95,10 @@ def test_base_merge_every_vector_width_and_launch_shape(elem_bytes, d):
                                    (0, 0, 17), (256, 4, 0), (0, 0, 10000)]:
         check_base(cfg, insts, 2, 1, 0, bound=bound,
                    tune={ab.TUNE_KV_THREADS: threads, ab.TUNE_KV_UNROLL: unroll})
+    # per-pass grids: exact local bound (10 blocks of 17), too small, larger than the whole
+    for local in (10, 1, 40):
+        check_base(cfg, insts, 2, 1, 0, bound=17, local_bound=local)
+    check_base(cfg, insts, 2, 1, 1, bound=0, local_bound=7)    # a local bound alone changes nothing
 
 
 def test_base_merge_degenerate_and_error_cases():
@@ -154,7 +158,8 @@ def test_base_merge_4xTP1_to_TP4_at_7b_block_shape(lay):
     cfg, insts = instances(m, k, per, n_heads=w.n_kv_heads, d=w.head_dim, B=16, layers=2,
                            P=int(nb_max * 1.1) + 1, W=W, seed=12)
     total = sum(int(((x.astype(np.int64) + 15) // 16).sum()) for x in per)
-    check_base(cfg, insts, m, k, 1, lay=lay, bound=total)
+    local = int(((per[1].astype(np.int64) + 15) // 16).sum())
+    check_base(cfg, insts, m, k, 1, lay=lay, bound=total, local_bound=local)
 
 
 @pytest.mark.parametrize("seed", range(12))
@@ -176,4 +181,5 @@ def test_base_merge_random_shapes(seed):
     lay = (int(rng.integers(0, 2)), int(rng.integers(0, 2)))
     total = sum(sum((x + B - 1) // B for x in row) for row in lens)
     check_base(cfg, insts, m, k, int(rng.integers(0, k * m)), lay=lay,
-               slack=int(rng.integers(0, 5)), bound=total if seed % 2 else 0)
+               slack=int(rng.integers(0, 5)), bound=total if seed % 2 else 0,
+               local_bound=int(rng.integers(0, total + 2)) if seed % 3 else 0)
