@@ -28,8 +28,8 @@ PEAK_HBM_GBPS = 8000.0  # MI355X HBM3E, published peak
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="all",
                     help="all (default): the four 7B-and-larger configurations in one run, the "
                          "headline being the largest (llama13b); or one of tiny, llama7b, "

@@ -39,6 +39,17 @@ __device__ __forceinline__ void st(char* p, V v) {
     *g = v;
 }
 
+// A pointer that is the same for every lane (a kernel argument), pinned in scalar registers.
+// Without this, a per-lane choice between two pointer arguments is compiled as a choice
+// between their ADDRESSES in the argument block followed by a vector load of the chosen
+// pointer: one more memory latency in front of every data load.
+__device__ __forceinline__ const char* uniform_ptr(const char* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(v));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(v >> 32));
+  return reinterpret_cast<const char*>((uint64_t(hi) << 32) | lo);
+}
+
 // XCD-aware work order.  Workgroups are dealt to the 8 XCDs (each with its own L2) round
 // robin by workgroup id, so with work item = workgroup id the XCDs interleave on chunks of
 // one tile.  Giving XCD x the x-th contiguous eighth of the items instead lets each XCD

@@ -230,6 +230,8 @@ __device__ __forceinline__ void regroup_tile(const KVArgs& a, uint32_t layer, ui
   const char* sp[UNROLL];
   uint32_t dvec[UNROLL];
   bool live[UNROLL];
+  const char* const pool_lo = uniform_ptr(a.src_lo);
+  const char* const pool_hi = uniform_ptr(a.src_hi);
 #pragma unroll
   for (int u = 0; u < UNROLL; ++u) {
     const uint32_t v = tile * kTileVecs + u * THREADS + tid;
@@ -257,13 +259,13 @@ __device__ __forceinline__ void regroup_tile(const KVArgs& a, uint32_t layer, ui
                               ? hs * a.head_vecs.d + within
                               : (ct * a.heads_src.d + hs) * a.dv.d + x;
     // Source pool of the owning rank.  Nearly always one or two ranks feed a target
-    // rank; then the choice is a select between two scalar-loaded pointers and
-    // costs no memory access.
+    // rank; then the choice is a select between two pointers held in scalar registers
+    // and costs no memory access.
     const char* pool;
     if (one_pool)  // merge: every head of the block comes from the block's instance
       pool = one_pool;
     else if (a.n_src <= 2)
-      pool = (s == a.rank_lo) ? a.src_lo : a.src_hi;
+      pool = (s == a.rank_lo) ? pool_lo : pool_hi;
     else
       pool = a.src[live[u] ? s : a.rank_lo];  // s < src_tp on live lanes
     sp[u] = pool + uint64_t(svec) * VEC;
@@ -451,6 +453,8 @@ kv_regroup_staged_kernel(const KVArgs a, const KVStagedGeom g, const int32_t* __
   const uint32_t n_items = total * a.tiles_per_block.d;
   const uint32_t dv = a.dv.d, B = g.block_tokens;
   const uint32_t n_loop = xcd_loop_bound(n_items);  // XCD-chunked order, see xcd_item()
+  const char* const pool_lo = uniform_ptr(a.src_lo);
+  const char* const pool_hi = uniform_ptr(a.src_hi);
 
   for (uint32_t wi = blockIdx.x; wi < n_loop; wi += gridDim.x) {
     const uint32_t w = xcd_item(wi, n_items);
@@ -479,7 +483,7 @@ kv_regroup_staged_kernel(const KVArgs a, const KVStagedGeom g, const int32_t* __
         const uint32_t hg = a.head0 + hp;
         const uint32_t s = fd_div(hg, a.heads_src);
         const uint32_t hs = hg - s * a.heads_src.d;
-        const char* pool = (a.n_src <= 2) ? ((s == a.rank_lo) ? a.src_lo : a.src_hi) : a.src[s];
+        const char* pool = (a.n_src <= 2) ? ((s == a.rank_lo) ? pool_lo : pool_hi) : a.src[s];
         const uint32_t sv = block_vec<SL>(hs, c, t0 + t, x, a.heads_src.d, B, dv);
         val[u] = ld<NT, u32x4>(pool + soff + uint64_t(sv) * 16);
         slot[u] = (t * g.tile_heads + h) * dv + x;
