@@ -227,6 +227,7 @@ __device__ __forceinline__ void regroup_tile(const KVArgs& a, uint32_t layer, ui
                                              const char* one_pool = nullptr) {
   using V = typename VecOf<VEC>::type;
   constexpr uint32_t kTileVecs = THREADS * UNROLL;
+  if (sb < 0) return;  // uniform: the block's source id was out of range
   const char* sp[UNROLL];
   uint32_t dvec[UNROLL];
   bool live[UNROLL];
@@ -234,8 +235,12 @@ __device__ __forceinline__ void regroup_tile(const KVArgs& a, uint32_t layer, ui
   const char* const pool_hi = uniform_ptr(a.src_hi);
 #pragma unroll
   for (int u = 0; u < UNROLL; ++u) {
-    const uint32_t v = tile * kTileVecs + u * THREADS + tid;
-    live[u] = v < a.block_vecs;
+    // Lanes past the end of a ragged last tile are clamped to the block's last vector for
+    // the load (valid memory, value unused) and only masked for the store: loads inside
+    // per-lane branches are separated by waits, which would serialise the UNROLL loads.
+    const uint32_t v_raw = tile * kTileVecs + u * THREADS + tid;
+    live[u] = v_raw < a.block_vecs;
+    const uint32_t v = min(v_raw, a.block_vecs - 1);
     dvec[u] = v;
     uint32_t hp, within, ct = 0, x = 0;  // within: index inside one header-centric head
     if (DL == AMOEBA_KV_HEAD_MAJOR) {
@@ -267,16 +272,19 @@ __device__ __forceinline__ void regroup_tile(const KVArgs& a, uint32_t layer, ui
     else if (a.n_src <= 2)
       pool = (s == a.rank_lo) ? pool_lo : pool_hi;
     else
-      pool = a.src[live[u] ? s : a.rank_lo];  // s < src_tp on live lanes
+      pool = a.src[s];  // s < src_tp: v is a vector of the block
     sp[u] = pool + uint64_t(svec) * VEC;
   }
   const uint64_t soff = uint64_t(layer) * a.src_layer_stride + uint64_t(sb) * a.src_block_bytes;
   char* dp = a.dst + uint64_t(layer) * a.dst_layer_stride + uint64_t(b) * a.dst_block_bytes;
   V val[UNROLL];
 #pragma unroll
-  for (int u = 0; u < UNROLL; ++u) {
-    live[u] = live[u] && sb >= 0;
-    if (live[u]) val[u] = ld<NT, V>(sp[u] + soff);
+  for (int u = 0; u < UNROLL; ++u) val[u] = ld<NT, V>(sp[u] + soff);
+  if constexpr (VEC == 16) {
+    // pin the loads here, unconditional and back to back (otherwise the compiler sinks each
+    // one into the masked block of its store)
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) asm volatile("" : "+v"(val[u]));
   }
 #pragma unroll
   for (int u = 0; u < UNROLL; ++u)

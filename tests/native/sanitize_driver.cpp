@@ -162,6 +162,29 @@ static void merge_case(int m, int k) {
   }
 }
 
+static void merge_base_case(int m, int k, int lay_s, int lay_d) {
+  const int32_t lens[4][3] = {{13, 1, 8}, {5, 22, 3}, {16, 2, 7}, {1, 1, 9}};
+  int64_t total = 0;
+  for (int g = 0; g < m; ++g) for (int i = 0; i < 3; ++i) total += (lens[g][i] + 3) / 4;
+  ao_kv c = {2, 8, 4, 2, 4, lay_s, lay_d, 3, 6, 12, total + 1};
+  std::vector<std::vector<int32_t>> tables(m, std::vector<int32_t>(18, -1));
+  for (int g = 0; g < m; ++g) { int next = (g * 5) % 12; for (int i = 0; i < 3; ++i) for (int j = 0; j < (lens[g][i] + 3) / 4; ++j) { tables[g][i * 6 + j] = next; next = (next + 1) % 12; } }
+  const int64_t be_s = ao_kv_block_elems(&c, k), be_d = ao_kv_block_elems(&c, k * m);
+  for (int rp = 0; rp < k * m; ++rp) {
+    std::vector<std::vector<uint16_t>> pools(m);
+    std::vector<const void*> pp(m);
+    std::vector<const int32_t*> tp(m), lp(m);
+    for (int g2 = 0; g2 < m; ++g2) { pools[g2] = random_u16(size_t(2 * 12 * be_s), 300 + g2); pp[g2] = pools[g2].data(); tp[g2] = tables[g2].data(); lp[g2] = lens[g2]; }
+    const size_t n = size_t(2 * (total + 1) * be_d), guard = 64;
+    std::vector<uint16_t> fresh(n + 2 * guard, 0xABCD);
+    std::vector<int32_t> out(size_t(m * 18));
+    int64_t mig = -1, dfr = -1;
+    CHECK(ao_merge_kv_base(&c, k, m, rp, pp.data(), tp.data(), lp.data(), fresh.data() + guard, out.data(), &mig, &dfr) == AO_OK);
+    CHECK(mig + dfr == total);
+    for (size_t i = 0; i < guard; ++i) CHECK(fresh[i] == 0xABCD && fresh[guard + n + i] == 0xABCD);
+  }
+}
+
 int main() {
   const int tps[][2] = {{1, 1}, {1, 2}, {2, 1}, {1, 4}, {4, 1}, {2, 4}, {4, 2}, {2, 2}};
   for (auto& t : tps) {
@@ -176,6 +199,7 @@ int main() {
     for (int ls = 0; ls < 2; ++ls) for (int ld = 0; ld < 2; ++ld) kv_case(t[0], t[1], ls, ld);
   }
   merge_case(4, 1); merge_case(2, 2); merge_case(2, 1);
+  for (int ls = 0; ls < 2; ++ls) for (int ld = 0; ld < 2; ++ld) { merge_base_case(4, 1, ls, ld); merge_base_case(2, 2, ls, ld); }
   std::printf("sanitize driver: %d failure(s)\n", failures);
   return failures ? 1 : 0;
 }

@@ -22,7 +22,12 @@ def _announce(request):
     yield
 
 
-def test_weights_and_kv_replay_from_a_captured_graph():
+@pytest.mark.parametrize("static", [False, True])
+@pytest.mark.parametrize("three_kernels", [False, True])
+def test_weights_and_kv_replay_from_a_captured_graph(static, three_kernels):
+    """static: the KV call is the entry point that allocates nothing (its reason to exist is code
+    under capture).  three_kernels: the scan / table / regroup path instead of the one-launch path
+    this small table would take."""
     B, d, H, layers = 16, 64, 8, 3
     lens0 = np.array([40, 100, 7, 33, 0, 16], dtype=np.int32)
     nb = (lens0.astype(np.int64) + B - 1) // B
@@ -41,6 +46,9 @@ def test_weights_and_kv_replay_from_a_captured_graph():
     m = model_for_kv(kv)
     k, kp, rp = 2, 1, 0
     plan = ab.amoeba_plan(shape_from(m, kv), k, kp, rp)
+    if three_kernels:
+        ab.amoeba_plan_tune(plan, ab.TUNE_KV_SMALL_TABLE, 1)
+    reshard_kv = ab.amoeba_reshard_kv_static if static else ab.amoeba_reshard_kv
 
     n_src = oracle.shard_elems(m, k)
     w_src_np = [wl.random_bits(n_src, seed=70 + s) for s in range(k)]
@@ -69,14 +77,14 @@ def test_weights_and_kv_replay_from_a_captured_graph():
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
         ab.amoeba_reshard_weights(plan, w_src, w_dst)
-        ab.amoeba_reshard_kv(plan, pools, table_d, lens_d, kv_dst, out_table)
+        reshard_kv(plan, pools, table_d, lens_d, kv_dst, out_table)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
 
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         ab.amoeba_reshard_weights(plan, w_src, w_dst)
-        ab.amoeba_reshard_kv(plan, pools, table_d, lens_d, kv_dst, out_table)
+        reshard_kv(plan, pools, table_d, lens_d, kv_dst, out_table)
 
     for it in range(4):
         # eager work between replays: wipe the outputs and change the lengths in place, so a
