@@ -93,6 +93,7 @@ def main():
         return overlap(args)
 
     if args.workload != "all":
+        warm_up_device()
         out = reshard(args, args.workload, cpu_budget_s=0 if args.no_cpu_baseline else 12.0)
         print(json.dumps(out), flush=True)
         return
@@ -101,6 +102,7 @@ def main():
     # timed steps) on its own pools, which are freed before the next one is built.
     rows = []
     head = None
+    warm_up_device()
     for name in DEFAULT_SET:
         is_head = name == HEADLINE
         budget = 0 if args.no_cpu_baseline else (15.0 if is_head else 4.0)
@@ -112,6 +114,25 @@ def main():
         rows.append(summary_row(name, out))
     head["configs"] = rows
     print(json.dumps(head), flush=True)
+
+
+def warm_up_device():
+    """About a third of a second of streaming copies before the first configuration: the first
+    kernels after process start run below the sustained rate (clocks and power state ramp up),
+    which would otherwise be charged to whichever configuration comes first."""
+    import torch
+
+    from paper_2509_19729_amd import binding as ab
+    a = torch.empty(1 << 28, dtype=torch.int32, device="cuda")
+    b = torch.empty_like(a)
+    a.zero_()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < 0.3:
+        for _ in range(20):
+            ab.amoeba_copy_baseline(b, a, a.numel() * 4, 64, 1, 0, 1)
+        torch.cuda.synchronize()
+    del a, b
+    torch.cuda.empty_cache()
 
 
 def summary_row(name, out):
