@@ -262,7 +262,8 @@ int amoeba_kv_status(const amoeba_plan_t* plan, void* stream, int64_t* total_blo
  * amoeba_plan_merge_factor(plan) = m >= 2 (dst_pool_blocks is not used).  Enqueues three
  * kernels, no host synchronisation, no extra device memory beyond the plan's workspace
  * (about 8*m*src_pool_blocks bytes: a flag and a work-list entry per new block id).
- * Device-found conditions are read
+ * For this call the shape's kv_blocks_bound, if set, bounds the blocks that move, i.e. those
+ * of the other instances (the local ones stay where they are).  Device-found conditions are read
  * with amoeba_merge_kv_status(): AMOEBA_ERR_OVERFLOW (negative length / row too short:
  * nothing written, table all -1), AMOEBA_ERR_BLOCK_ID (an id outside the pool: entry -1,
  * block skipped).  Calls on one plan must not overlap in time.
