@@ -456,6 +456,12 @@ def weights_padded(args):
     ms = timed(p_dense, src, dst)
     res["scale_up_dense_partial_swap"] = {"ms": round(ms, 4),
                                           "bytes_copied": ab.amoeba_plan_shard_bytes(p_dense, 1)}
+    # the paper keeps the attention weights duplicated and swaps the FFN partition only
+    # (Sec. 3.2): the same copy restricted to the FFN tensors
+    ms_ffn = timed(p_dense, src, dst, ab.PART_FFN)
+    t = [ab.amoeba_plan_tensor_info(p_dense, 1, x) for x in (ab.T_GATE, ab.T_UP, ab.T_DOWN)]
+    ffn_bytes = sum(r * c for _, r, c, _ in t) * 2 * max(1, w.n_experts // 4) * w.n_layers
+    res["scale_up_dense_partial_swap_ffn_only"] = {"ms": round(ms_ffn, 4), "bytes_copied": ffn_bytes}
     del src, dst
     torch.cuda.empty_cache()
     p_pad = ab.amoeba_plan(shape(1, 1), 1, 4, 1)
