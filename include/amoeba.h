@@ -66,7 +66,8 @@ extern "C" {
 enum { AMOEBA_KV_HEAD_MAJOR = 0, AMOEBA_KV_TOKEN_MAJOR = 1 };
 
 /*
- * AMOEBA_W_FFN_PADDED: the layout of Sec. 3.2, Improvement 1 ("parallelism-aware padding").
+ * AMOEBA_W_FFN_PADDED: the layout of Sec. 3.2, Improvement 1 (weight padding at the partition
+ * boundaries).
  * Every FFN tensor is cut in T = pad_max_tp partitions (gate/up by stored rows, down by
  * stored columns) and padding is added at every potential TP boundary so that each
  * partition starts on a multiple of pad_page_bytes.  A rank at TP = t stores, per layer,
@@ -335,7 +336,8 @@ int amoeba_plan_tensor_info(const amoeba_plan_t* plan, int side, int tensor, int
  * padded, one tensor-partition, one tensor-partition padded, partition stride, layer}.
  * AMOEBA_ERR_INVALID_ARG if that side is dense. */
 int amoeba_plan_padded_info(const amoeba_plan_t* plan, int side, int64_t out[6]);
-/* Zero-copy scale-up (Sec. 3.2: "directly release unused pages").  If both sides are padded
+/* Zero-copy scale-up (Sec. 3.2, Improvement 1: with the padding in place a split only has to
+ * release pages).  If both sides are padded
  * and src_tp divides dst_tp, the target's FFN partitions are one page-aligned byte range of
  * every layer of source rank out[0]: out = {source rank, byte offset of the range inside a
  * source layer, bytes of the range, source layer bytes}.  Returns 1 if such a view exists,
