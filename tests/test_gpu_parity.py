@@ -285,6 +285,31 @@ def test_kv_more_than_one_scan_chunk():
     check_kv(cfg, 1, 2, 1, pools, table, lens)
 
 
+@pytest.mark.parametrize("n_seqs,longest", [(64, 62 * 4), (64, 63 * 4), (65, 40), (63, 62 * 4 - 3)])
+def test_kv_small_table_boundaries(n_seqs, longest):
+    """Around the limits of the one-launch path (64 sequences, 4096 table cells: 64 rows of 64):
+    exactly at them, one row too wide, one sequence too many.  check_kv runs the path the
+    library picks and the forced three-kernel path; both must equal the oracle."""
+    rng = np.random.default_rng(n_seqs + longest)
+    lens = rng.integers(0, 30, size=n_seqs)
+    lens[n_seqs // 2] = longest            # fixes the table width: blocks of the longest + 2
+    lens[-1] = 17                          # the last lane of the scan owns blocks too
+    for lay_s, lay_d in [(HM, HM), (TM, HM)]:
+        cfg, pools, table, lens_ = kv_case(2, lens, lay_s, lay_d, n_heads=4, d=8, B=4, layers=2,
+                                           seed=longest)
+        plan = ab.amoeba_plan(ab.ModelShape(2, 32, 4, 4, 8, 64, kv_block_tokens=4, kv_layers=2,
+                                            num_seqs=cfg.num_seqs,
+                                            max_blocks_per_seq=cfg.max_blocks_per_seq,
+                                            src_pool_blocks=cfg.src_pool_blocks,
+                                            dst_pool_blocks=cfg.dst_pool_blocks), 2, 1, 0)
+        lanes = ab.amoeba_plan_launch_shape(plan, ab.KERNEL_KV_REGROUP, 16)[2]
+        small = cfg.num_seqs <= 64 and cfg.num_seqs * cfg.max_blocks_per_seq <= 4096
+        assert lanes == (64 if small else 256)     # no bound given: 256 lanes unless one launch
+        plan.close()
+        check_kv(cfg, 2, 1, 0, pools, table, lens_)
+        check_kv(cfg, 2, 4, 3, pools, table, lens_)
+
+
 def test_kv_degenerate_inputs():
     # all sequences empty
     cfg, pools, table, lens = kv_case(1, [0, 0, 0], HM, HM)
